@@ -1,0 +1,145 @@
+"""ctypes front end of the C oracle, plus the selection step in numpy.
+
+Test infrastructure only (see the package docstring)."""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pdd_oracle.c")
+_LIB = os.path.join(_HERE, "libpdd_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile pdd_oracle.c with gcc (generic x86-64, no fast-math, no FMA
+    contraction) into libpdd_oracle.so next to it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        lib.pddo_attention.restype = ctypes.c_int
+        lib.pddo_attention.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int, i32p, i32p, ctypes.c_double, ctypes.c_int,
+                                       i32p, f64p, f64p]
+        lib.pddo_importance.restype = ctypes.c_int
+        lib.pddo_importance.argtypes = [u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                        ctypes.c_int, i32p, i32p, ctypes.c_double, ctypes.c_int,
+                                        f64p]
+        lib.pddo_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().pddo_num_threads())
+
+
+def widen_bf16(bits: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns -> float64, exactly."""
+    u = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def _ptr(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _check_inputs(q, k, v, cu_q, cu_k):
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    k = np.ascontiguousarray(k, dtype=np.uint16)
+    v = None if v is None else np.ascontiguousarray(v, dtype=np.uint16)
+    cu_q = np.ascontiguousarray(cu_q, dtype=np.int32)
+    cu_k = np.ascontiguousarray(cu_k, dtype=np.int32)
+    assert q.ndim == 3 and k.ndim == 3 and q.shape[2] == k.shape[2]
+    assert q.shape[0] == cu_q[-1] and k.shape[0] == cu_k[-1] and len(cu_q) == len(cu_k)
+    if v is not None:
+        assert v.shape == k.shape
+    return q, k, v, cu_q, cu_k
+
+
+def attention(q, k, v, cu_q, cu_k, scale: float, rows: Optional[Sequence[int]] = None):
+    """O [n_rows, Hq, d] and LSE [Hq, n_rows] (float64) for the packed query
+    rows `rows` (default: all)."""
+    q, k, v, cu_q, cu_k = _check_inputs(q, k, v, cu_q, cu_k)
+    B = len(cu_q) - 1
+    Hq, d, Hkv = q.shape[1], q.shape[2], k.shape[1]
+    if rows is None:
+        rows_arr, n_rows, rows_ptr = None, q.shape[0], None
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int32)
+        n_rows, rows_ptr = len(rows_arr), _ptr(rows_arr, ctypes.c_int32)
+    O = np.empty((n_rows, Hq, d), dtype=np.float64)
+    lse = np.empty((Hq, n_rows), dtype=np.float64)
+    rc = _load().pddo_attention(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16),
+                                _ptr(v, ctypes.c_uint16), B, Hq, Hkv, d,
+                                _ptr(cu_q, ctypes.c_int32), _ptr(cu_k, ctypes.c_int32),
+                                float(scale), n_rows, rows_ptr,
+                                _ptr(O, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("oracle attention: bad arguments")
+    return O, lse
+
+
+def importance(q, k, cu_q, cu_k, scale: float, window: int) -> np.ndarray:
+    """imp [Hkv, total_k] float64.  window < 0: every query is a window query."""
+    q, k, _, cu_q, cu_k = _check_inputs(q, k, None, cu_q, cu_k)
+    B = len(cu_q) - 1
+    Hq, d, Hkv = q.shape[1], q.shape[2], k.shape[1]
+    imp = np.empty((Hkv, k.shape[0]), dtype=np.float64)
+    rc = _load().pddo_importance(_ptr(q, ctypes.c_uint16), _ptr(k, ctypes.c_uint16),
+                                 B, Hq, Hkv, d, _ptr(cu_q, ctypes.c_int32),
+                                 _ptr(cu_k, ctypes.c_int32), float(scale), int(window),
+                                 _ptr(imp, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("oracle importance: bad arguments")
+    return imp
+
+
+def select_topk(scores: np.ndarray, cu_k, k_per_seq, cand_begin=None, cand_end=None):
+    """Top-k selection per (KV head, sequence).
+
+    Candidates of sequence b are its keys [cand_begin[b], cand_end[b]) (default:
+    all).  They are ordered by (score descending, index ascending); the first
+    k_per_seq[b] are kept and reported in ascending index order
+    (sequence-local).  Returns (indices [Hkv, sum k], mask uint8 [Hkv, total_k]).
+    """
+    scores = np.asarray(scores)
+    cu_k = np.asarray(cu_k, dtype=np.int64)
+    B = len(cu_k) - 1
+    Hkv = scores.shape[0]
+    k_per_seq = np.asarray(k_per_seq, dtype=np.int64)
+    cu_keep = np.concatenate([[0], np.cumsum(k_per_seq)])
+    idx_out = np.zeros((Hkv, int(cu_keep[-1])), dtype=np.int32)
+    mask = np.zeros((Hkv, int(cu_k[-1])), dtype=np.uint8)
+    for g in range(Hkv):
+        for b in range(B):
+            n = int(cu_k[b + 1] - cu_k[b])
+            c0 = 0 if cand_begin is None else int(cand_begin[b])
+            c1 = n if cand_end is None else int(cand_end[b])
+            kb = int(k_per_seq[b])
+            if not (0 <= c0 <= c1 <= n) or kb > c1 - c0 or kb < 0:
+                raise ValueError("bad candidate range or k")
+            cand = np.arange(c0, c1)
+            s = scores[g, cu_k[b] + c0: cu_k[b] + c1]
+            order = np.lexsort((cand, -s))          # primary: -score, then index
+            keep = np.sort(cand[order[:kb]])
+            idx_out[g, cu_keep[b]:cu_keep[b + 1]] = keep
+            mask[g, cu_k[b] + keep] = 1
+    return idx_out, mask

@@ -1,0 +1,314 @@
+"""Pins for the CPU oracle: values fixed by the paper's definitions and by
+mathematics, none of them produced by the oracle itself or by the GPU path."""
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from brute import brute_packed, brute_topk
+
+GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "handworked.json")))
+LN2 = float(np.log(2.0))
+
+
+def bits(x):
+    """float array -> bf16 bits, asserting that nothing is lost."""
+    x = np.asarray(x, dtype=np.float32)
+    b = W.f32_to_bf16_bits(x)
+    assert np.array_equal(W.bf16_bits_to_f32(b), x), "test input must be exact in bf16"
+    return b
+
+
+def fr(xs):
+    return np.array([float(Fraction(s)) for s in xs])
+
+
+def cu(lens):
+    return np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+
+
+# ---------------------------------------------------------------- hand-worked
+def _case1_inputs():
+    c = GOLD["case1"]
+    q = bits(np.array(c["q"], dtype=np.float32).reshape(4, 1, 1))
+    k = bits(np.array(c["k"], dtype=np.float32).reshape(4, 1, 1))
+    v = bits(np.array(c["v"], dtype=np.float32).reshape(4, 1, 1))
+    return q, k, v
+
+
+def test_handworked_case1_attention():
+    c = GOLD["case1"]
+    q, k, v = _case1_inputs()
+    O, lse = oracle.attention(q, k, v, cu([4]), cu([4]), LN2)
+    np.testing.assert_allclose(O[:, 0, 0], fr(c["O"]), rtol=1e-13)
+    np.testing.assert_allclose(np.exp(lse[0]), c["exp_LSE"], rtol=1e-13)
+
+
+def test_handworked_case1_rows_of_P():
+    """Row i of P is read back through V = e_j (one-hot values): O[i] = P[i,j]."""
+    c = GOLD["case1"]
+    q, k, _ = _case1_inputs()
+    for j in range(4):
+        v = np.zeros((4, 1, 1), dtype=np.float32)
+        v[j] = 1.0
+        O, _ = oracle.attention(q, k, bits(v), cu([4]), cu([4]), LN2)
+        for i in range(4):
+            want = float(Fraction(c["P_rows"][i][j])) if j <= i else 0.0
+            assert abs(O[i, 0, 0] - want) < 1e-14
+
+
+def test_handworked_case1_importance_and_selection():
+    c = GOLD["case1"]
+    q, k, _ = _case1_inputs()
+    imp2 = oracle.importance(q, k, cu([4]), cu([4]), LN2, 2)
+    np.testing.assert_allclose(imp2[0], fr(c["W2_imp"]), rtol=1e-13)
+    imp4 = oracle.importance(q, k, cu([4]), cu([4]), LN2, 4)
+    np.testing.assert_allclose(imp4[0], fr(c["W4_imp"]), rtol=1e-13)
+    assert abs(imp4.sum() - 4.0) < 1e-12
+    # selection on the exact fractions (ties 0 vs 2 are exact there)
+    exact = fr(c["W2_imp"])[None, :]
+    idx, mask = oracle.select_topk(exact, cu([4]), [2])
+    assert idx[0].tolist() == c["W2_top2"] and mask[0].tolist() == [0, 1, 0, 1]
+    idx, mask = oracle.select_topk(exact, cu([4]), [3])
+    assert idx[0].tolist() == c["W2_top3"] and mask[0].tolist() == [1, 1, 0, 1]
+
+
+def test_handworked_case2_gqa_group_sum():
+    c = GOLD["case2_gqa"]
+    q1, k, _ = _case1_inputs()
+    q = np.zeros((4, 2, 1), dtype=np.uint16)
+    q[:, 0, :] = q1[:, 0, :]                      # head A = case 1, head B = 0
+    imp = oracle.importance(q, k, cu([4]), cu([4]), LN2, 2)
+    np.testing.assert_allclose(imp[0], fr(c["imp_group"]), rtol=1e-13)
+    assert abs(imp.sum() - c["sum"]) < 1e-12
+    qB = np.zeros((4, 1, 1), dtype=np.uint16)
+    impB = oracle.importance(qB, k, cu([4]), cu([4]), LN2, 2)
+    np.testing.assert_allclose(impB[0], fr(c["imp_B"]), rtol=1e-13)
+
+
+def test_handworked_case3_chunked():
+    c = GOLD["case3_chunked"]
+    q, k, v = _case1_inputs()
+    qc = q[2:]
+    O, lse = oracle.attention(qc, k, v, cu([2]), cu([4]), LN2)
+    np.testing.assert_allclose(O[:, 0, 0], fr(c["O"]), rtol=1e-13)
+    np.testing.assert_allclose(np.exp(lse[0]), c["exp_LSE"], rtol=1e-13)
+    imp = oracle.importance(qc, k, cu([2]), cu([4]), LN2, -1)
+    np.testing.assert_allclose(imp[0], fr(c["imp_all"]), rtol=1e-13)
+    idx, mask = oracle.select_topk(fr(c["imp_all"])[None, :], cu([4]), [1],
+                                   cand_begin=[0], cand_end=[2])
+    assert idx[0].tolist() == c["top1_of_prefix"] and mask[0].tolist() == [0, 1, 0, 0]
+
+
+# ---------------------------------------------------------------- brute force
+@pytest.mark.parametrize("seqs_q,seqs_k,hq,hkv,d,window,seed", [
+    ([17], None, 1, 1, 8, 5, 0),
+    ([33, 1, 20], None, 4, 2, 16, 7, 1),          # ragged, GQA, a length-1 prompt
+    ([9, 14], None, 6, 2, 4, 64, 2),              # window longer than the prompt
+    ([5, 8], [21, 8], 4, 1, 8, -1, 3),            # chunk vs prefix, all rows window
+    ([6], [40], 2, 2, 32, 3, 4),                  # chunk + finite window
+])
+def test_oracle_matches_materialised_softmax(seqs_q, seqs_k, hq, hkv, d, window, seed):
+    wl = W.make_custom("t", seqs_q, seqs_k, hq, hkv, d, max(window, 0), seed=seed)
+    O, lse = oracle.attention(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale)
+    imp = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, window)
+    bO, bL, bI = brute_packed(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k,
+                              wl.scale, window)
+    np.testing.assert_allclose(O, bO, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(lse, bL, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(imp, bI, rtol=1e-11, atol=1e-13)
+
+
+def test_row_subset_equals_full_rows():
+    wl = W.make_custom("t", [23, 12], None, 4, 2, 16, 4, seed=7)
+    O, lse = oracle.attention(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale)
+    rows = [34, 0, 22, 23, 5]
+    Os, ls = oracle.attention(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale,
+                              rows=rows)
+    assert np.array_equal(Os, O[rows]) and np.array_equal(ls, lse[:, rows])
+
+
+# ------------------------------------------------- closed forms / invariants
+def _harmonic(n):
+    return sum(1.0 / t for t in range(1, n + 1))
+
+
+def test_uniform_case_closed_form():
+    """Q = 0: every visible key gets 1/(i+delta+1); O is the running mean of V;
+    LSE_i = ln(i+delta+1); importance is a difference of harmonic numbers."""
+    n, hq, hkv, d, w = 40, 4, 2, 8, 12
+    wl = W.make_custom("t", [n], None, hq, hkv, d, w, seed=11)
+    q0 = np.zeros_like(wl.q)
+    O, lse = oracle.attention(q0, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale)
+    v = W.bf16_bits_to_f32(wl.v).astype(np.float64)
+    run_mean = np.cumsum(v, axis=0) / np.arange(1, n + 1)[:, None, None]
+    for h in range(hq):
+        np.testing.assert_allclose(O[:, h], run_mean[:, h // 2], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(lse[h], np.log(np.arange(1, n + 1)), rtol=1e-13, atol=1e-14)
+    imp = oracle.importance(q0, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, w)
+    HN = _harmonic(n)
+    want = np.array([(hq // hkv) * (HN - _harmonic(max(j, n - w))) for j in range(n)])
+    for g in range(hkv):
+        np.testing.assert_allclose(imp[g], want, rtol=1e-12)
+    # an all-ties prefix: tie rule keeps the lowest indices
+    idx, _ = oracle.select_topk(imp, wl.cu_seqlens_k, [10])
+    assert idx[0].tolist() == list(range(10))
+
+
+def test_row0_and_single_token_prompts_give_the_dot_product():
+    """A prompt of one token: P = [1], O = v, LSE = scale * <q, k>  (checks the
+    contraction against numpy's matmul on the widened inputs)."""
+    b, hq, hkv, d = 12, 4, 2, 32
+    wl = W.make_custom("t", [1] * b, None, hq, hkv, d, 1, seed=5)
+    O, lse = oracle.attention(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, 0.37)
+    q = W.bf16_bits_to_f32(wl.q).astype(np.float64)
+    k = W.bf16_bits_to_f32(wl.k).astype(np.float64)
+    v = W.bf16_bits_to_f32(wl.v).astype(np.float64)
+    for h in range(hq):
+        want = 0.37 * np.einsum("bc,bc->b", q[:, h], k[:, h // 2])
+        np.testing.assert_allclose(lse[h], want, rtol=1e-13, atol=1e-14)
+        np.testing.assert_array_equal(O[:, h], v[:, h // 2])
+    imp = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, 0.37, 1)
+    np.testing.assert_allclose(imp, (hq // hkv) * np.ones_like(imp), rtol=1e-13)
+
+
+def test_rows_sum_to_one_and_importance_mass():
+    """V = 1 reads back the row sums; sum_j imp[g,j] = G * W_b per sequence."""
+    lens, hq, hkv, d, w = [30, 7, 19], 6, 3, 16, 10
+    wl = W.make_custom("t", lens, None, hq, hkv, d, w, seed=9)
+    ones = bits(np.ones(wl.v.shape, dtype=np.float32))
+    O, _ = oracle.attention(wl.q, wl.k, ones, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale)
+    np.testing.assert_allclose(O, 1.0, rtol=0, atol=1e-12)
+    imp = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, w)
+    assert (imp >= 0).all()
+    for b, n in enumerate(lens):
+        seg = imp[:, wl.cu_seqlens_k[b]:wl.cu_seqlens_k[b + 1]]
+        np.testing.assert_allclose(seg.sum(axis=1), (hq // hkv) * min(w, n), rtol=1e-12)
+    # W = N: the column sums of one head total N
+    wl1 = W.make_custom("t", [25], None, 1, 1, 8, 25, seed=10)
+    imp1 = oracle.importance(wl1.q, wl1.k, wl1.cu_seqlens_q, wl1.cu_seqlens_k, wl1.scale, 25)
+    assert abs(imp1.sum() - 25.0) < 1e-11
+
+
+def test_causal_mask_bounds_on_importance():
+    """Key j only receives mass from window queries i with i + delta >= j; the
+    last key is seen by the last query alone."""
+    n, hq, hkv, d, w = 24, 2, 1, 8, 6
+    wl = W.make_custom("t", [n], None, hq, hkv, d, w, seed=13)
+    imp = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, w)
+    for j in range(n):
+        n_seen_by = n - max(j, n - w)
+        assert imp[0, j] <= hq * n_seen_by + 1e-12
+    # read P[n-1, n-1] of each head through a one-hot V
+    v = np.zeros((n, 1, d), dtype=np.float32)
+    v[n - 1, 0, 0] = 1.0
+    O, _ = oracle.attention(wl.q, wl.k, bits(v), wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale,
+                            rows=[n - 1])
+    assert abs(imp[0, n - 1] - O[0, :, 0].sum()) < 1e-14
+    # a strictly later key than every window query is impossible here, but a
+    # chunk never attends past its own position: with delta = 3 the key at
+    # local index nq-1+delta+... does not exist; check delta handling instead
+    wlc = W.make_custom("t", [4], [9], 1, 1, 8, 0, seed=14, chunked=True)
+    impc = oracle.importance(wlc.q, wlc.k, wlc.cu_seqlens_q, wlc.cu_seqlens_k, wlc.scale, -1)
+    assert abs(impc.sum() - 4.0) < 1e-12
+    # the last three keys are seen by 3, 2, 1 chunk queries only
+    assert impc[0, 8] <= 1 and impc[0, 7] <= 2 and impc[0, 6] <= 3
+
+
+def test_key_shift_leaves_P_unchanged_and_moves_lse():
+    """k_j <- k_j + c for all j: P and O do not change, LSE_i grows by
+    scale * <q_i, c> (integers keep everything exact in bf16); a large shift
+    also exercises the max subtraction."""
+    rng = np.random.default_rng(21)
+    n, d = 20, 4
+    q = rng.integers(-2, 3, size=(n, 1, d)).astype(np.float32)
+    k = rng.integers(-3, 4, size=(n, 1, d)).astype(np.float32)
+    v = rng.integers(-8, 9, size=(n, 1, d)).astype(np.float32)
+    c = np.array([40, -24, 16, 56], dtype=np.float32)
+    O1, l1 = oracle.attention(bits(q), bits(k), bits(v), cu([n]), cu([n]), 0.5)
+    O2, l2 = oracle.attention(bits(q), bits(k + c), bits(v), cu([n]), cu([n]), 0.5)
+    np.testing.assert_allclose(O1, O2, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(l2[0] - l1[0], 0.5 * (q[:, 0, :] @ c), rtol=1e-11, atol=1e-11)
+    i1 = oracle.importance(bits(q), bits(k), cu([n]), cu([n]), 0.5, 5)
+    i2 = oracle.importance(bits(q), bits(k + c), cu([n]), cu([n]), 0.5, 5)
+    np.testing.assert_allclose(i1, i2, rtol=1e-10, atol=1e-13)
+
+
+def test_identities_chunked_ragged_gqa():
+    hq, hkv, d = 4, 2, 16
+    full = W.make_custom("t", [37], None, hq, hkv, d, 9, seed=17)
+    O, lse = oracle.attention(full.q, full.k, full.v, cu([37]), cu([37]), full.scale)
+    imp = oracle.importance(full.q, full.k, cu([37]), cu([37]), full.scale, 9)
+    # chunked(Q[P:]) == rows [P, N) of the full run, importance == W = chunk
+    P = 28
+    Oc, lc = oracle.attention(full.q[P:], full.k, full.v, cu([9]), cu([37]), full.scale)
+    ic = oracle.importance(full.q[P:], full.k, cu([9]), cu([37]), full.scale, -1)
+    assert np.array_equal(Oc, O[P:]) and np.array_equal(lc, lse[:, P:])
+    np.testing.assert_allclose(ic, imp, rtol=1e-14)
+    # packed == alone
+    two = W.make_custom("t", [11, 26], None, hq, hkv, d, 5, seed=18)
+    Ot, lt = oracle.attention(two.q, two.k, two.v, two.cu_seqlens_q, two.cu_seqlens_k, two.scale)
+    it = oracle.importance(two.q, two.k, two.cu_seqlens_q, two.cu_seqlens_k, two.scale, 5)
+    Oa, la = oracle.attention(two.q[11:], two.k[11:], two.v[11:], cu([26]), cu([26]), two.scale)
+    ia = oracle.importance(two.q[11:], two.k[11:], cu([26]), cu([26]), two.scale, 5)
+    assert np.array_equal(Ot[11:], Oa) and np.array_equal(lt[:, 11:], la)
+    assert np.array_equal(it[:, 11:], ia)
+    # GQA == MHA with repeated K,V ; group importance = sum over repeated heads
+    kr = np.repeat(full.k, hq // hkv, axis=1)
+    vr = np.repeat(full.v, hq // hkv, axis=1)
+    Om, lm = oracle.attention(full.q, kr, vr, cu([37]), cu([37]), full.scale)
+    im = oracle.importance(full.q, kr, cu([37]), cu([37]), full.scale, 9)
+    assert np.array_equal(Om, O) and np.array_equal(lm, lse)
+    np.testing.assert_allclose(im.reshape(hkv, hq // hkv, -1).sum(axis=1), imp, rtol=1e-13)
+
+
+# ---------------------------------------------------------------- selection
+def test_select_matches_rank_counting_with_ties():
+    rng = np.random.default_rng(3)
+    lens = [13, 1, 30]
+    scores = rng.integers(0, 6, size=(2, sum(lens))).astype(np.float64) / 4.0  # many ties
+    ks = [5, 1, 11]
+    idx, mask = oracle.select_topk(scores, cu(lens), ks)
+    cuk = cu(lens)
+    cukeep = np.concatenate([[0], np.cumsum(ks)])
+    for g in range(2):
+        for b in range(3):
+            row = scores[g, cuk[b]:cuk[b + 1]]
+            want = brute_topk(row, ks[b])
+            got = idx[g, cukeep[b]:cukeep[b + 1]]
+            assert got.tolist() == want.tolist()
+            assert (np.diff(got) > 0).all() if len(got) > 1 else True
+            m = mask[g, cuk[b]:cuk[b + 1]]
+            assert m.sum() == ks[b] and set(np.nonzero(m)[0]) == set(got)
+            if ks[b] < len(row):
+                assert row[got].min() >= np.delete(row, got).max()
+
+
+def test_select_candidate_range_and_edge_counts():
+    s = np.array([[9.0, 1.0, 5.0, 7.0, 3.0, 8.0]])
+    idx, mask = oracle.select_topk(s, cu([6]), [2], cand_begin=[1], cand_end=[5])
+    assert idx[0].tolist() == [2, 3] and mask[0].tolist() == [0, 0, 1, 1, 0, 0]
+    idx, mask = oracle.select_topk(s, cu([6]), [0])
+    assert idx.shape == (1, 0) and mask.sum() == 0
+    idx, mask = oracle.select_topk(s, cu([6]), [6])
+    assert idx[0].tolist() == [0, 1, 2, 3, 4, 5]
+    with pytest.raises(ValueError):
+        oracle.select_topk(s, cu([6]), [5], cand_begin=[1], cand_end=[5])
+
+
+# ---------------------------------------------------------------- workloads
+def test_workload_recipes():
+    assert W.c3_lengths_from_recipe() == W.C3_LENGTHS
+    assert [W.keep_count(n, r) for n, r in
+            [(512, "1/2"), (4096, "3/10"), (32768, "1/10"), (8192, "1/4"), (3, "1/10")]] == \
+        [256, 1228, 3276, 2048, 1]
+    c1 = W.make_workload("c1")
+    assert c1.causal_pairs() == 131328 and c1.window_pairs() == 15888
+    c5 = W.make_workload("c5", n_override=64)
+    assert c5.cand_end.tolist() == [64] * 4 and c5.seqlens_k.tolist() == [320] * 4
+    x = np.array([1.0, 1.00390625, 1.01171875, -3.5e-41], dtype=np.float32)
+    assert W.f32_to_bf16_bits(x).tolist()[:3] == [0x3F80, 0x3F80, 0x3F82]
