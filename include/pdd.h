@@ -1,0 +1,198 @@
+/*
+ * pdd.h -- C ABI of libpdd: causal prompt-prefill attention for gfx950 fused
+ * with extraction of the prompt-refinement data (token importance, top-k
+ * token selection).
+ *
+ * General conventions (all entry points)
+ *   - "DEVICE" pointers are HBM addresses on the current HIP device; "HOST"
+ *     pointers are ordinary process memory.  The caller owns every buffer; the
+ *     library never allocates, frees or keeps a pointer after returning.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns without synchronising.  The library
+ *     never reads device memory from the host.
+ *   - Arguments are validated on the host before anything is launched; on a
+ *     validation failure nothing has been enqueued.  The return value is the
+ *     only error channel; pdd_last_error() gives a thread-local message.
+ *   - Every output element that belongs to a sequence is overwritten; outputs
+ *     need not be initialised.  Results are deterministic run to run.
+ *   - bf16 tensors are raw 16-bit patterns; the innermost (head_dim) axis is
+ *     contiguous; all DEVICE tensor pointers and all strides*2 bytes must be
+ *     multiples of 16 bytes.
+ *   - NaN / Inf inputs: undefined results (no fault).
+ *
+ * Notation: B sequences; sequence b has Nq_b queries and Nk_b >= Nq_b keys,
+ * delta_b = Nk_b - Nq_b; Hq query heads, Hkv KV heads, G = Hq/Hkv; d =
+ * head_dim.  Query head h reads KV head h / G.  Indices i, j are local to the
+ * sequence.
+ */
+#ifndef PDD_H
+#define PDD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pdd_status {
+    PDD_OK = 0,
+    PDD_ERR_INVALID_ARG = -1, /* null pointer, bad size, Hq % Hkv != 0, misaligned, ... */
+    PDD_ERR_UNSUPPORTED = -2, /* head_dim not in {64, 128}                             */
+    PDD_ERR_WORKSPACE = -3,   /* workspace smaller than pdd_workspace_bytes()           */
+    PDD_ERR_HIP = -4          /* a HIP runtime call (launch) reported an error          */
+} pdd_status;
+
+typedef void *pdd_stream; /* hipStream_t */
+
+/*
+ * One attention layer over a packed (ragged) batch.
+ *   Q, O : [total_q, Hq, d]  bf16, addressed token*stride_tok + head*stride_head + c
+ *   K, V : [total_k, Hkv, d] bf16
+ * Strides are in elements.  cu_seqlens_q / cu_seqlens_k are DEVICE int32
+ * arrays of B+1 non-decreasing prefix sums starting at 0 and ending at
+ * total_q / total_k.  The optional HOST copies (may be NULL) let the library
+ * validate them (monotone, end totals, Nk_b >= Nq_b, within max_seqlen);
+ * without them a malformed device array is clamped to the totals, never
+ * followed out of bounds.
+ */
+typedef struct pdd_attn_desc {
+    int32_t batch;        /* B >= 1                                            */
+    int32_t n_q_heads;    /* Hq                                                */
+    int32_t n_kv_heads;   /* Hkv, divides Hq                                   */
+    int32_t head_dim;     /* d in {64, 128}                                    */
+    int32_t total_q;      /* sum of Nq_b                                       */
+    int32_t total_k;      /* sum of Nk_b                                       */
+    int32_t max_seqlen_q; /* >= max Nq_b (sizes the launch grid)               */
+    int32_t max_seqlen_k; /* >= max Nk_b                                       */
+    const int32_t *cu_seqlens_q;      /* DEVICE int32[B+1]                     */
+    const int32_t *cu_seqlens_k;      /* DEVICE int32[B+1]                     */
+    const int32_t *cu_seqlens_q_host; /* HOST copy or NULL                     */
+    const int32_t *cu_seqlens_k_host; /* HOST copy or NULL                     */
+    int64_t q_stride_tok, q_stride_head;
+    int64_t k_stride_tok, k_stride_head;
+    int64_t v_stride_tok, v_stride_head;
+    int64_t o_stride_tok, o_stride_head;
+    float softmax_scale;  /* s; <= 0 selects 1/sqrt(d)                         */
+    int32_t window;       /* W: observation window = last min(W, Nq_b) queries;
+                             0 = no importance output                          */
+} pdd_attn_desc;
+
+/* which_call values for pdd_workspace_bytes */
+enum {
+    PDD_CALL_PREFILL_ATTN = 0,
+    PDD_CALL_PREFILL_ATTN_CHUNKED = 1,
+    PDD_CALL_TOKEN_IMPORTANCE = 2,
+    PDD_CALL_SELECT_TOPK = 3
+};
+
+/*
+ * Causal prefill attention (paper Section 2.2.3, the scaled dot-product
+ * attention equation softmax(Q K^T / sqrt(h)) V with h read as the per-head
+ * dimension, under the autoregressive mask), fused with the refiner's data
+ * extraction (Section 3.2 "Prompt Refiner": the normalised attention weight of
+ * the observation window against the entire K, summed along the query
+ * dimension; Section 3.2 "Preliminaries": obtained inside the attention
+ * implementation, in place, without materialising or copying the weights).
+ *
+ *   S[i,j]   = s * <q[i,h,:], k[j,g,:]>       for 0 <= j <= i + delta_b
+ *   lse[h,i] = ln sum_j exp(S[i,j])                         (natural log)
+ *   o[i,h,:] = sum_j exp(S[i,j] - lse[h,i]) * v[j,g,:]
+ *   importance[g,j] = sum_{h in group g} sum_{i in window_b, i+delta_b >= j}
+ *                     exp(S[i,j] - lse[h,i])
+ *
+ * o          DEVICE bf16 [total_q, Hq, d] (strides from desc)          -- out
+ * lse        DEVICE fp32 [Hq, total_q] contiguous                      -- out
+ * importance DEVICE fp32 [Hkv, total_k] contiguous, or NULL (then W is
+ *            ignored); must be non-NULL when desc->window > 0          -- out
+ * workspace  DEVICE scratch of at least pdd_workspace_bytes(desc,
+ *            PDD_CALL_PREFILL_ATTN) bytes (may be NULL when that is 0).
+ * Requires Nq_b == Nk_b for every sequence when host copies are given (use the
+ * chunked entry point otherwise).
+ */
+pdd_status pdd_prefill_attn(const pdd_attn_desc *desc, const void *q, const void *k,
+                            const void *v, void *o, float *lse, float *importance,
+                            void *workspace, size_t workspace_bytes, pdd_stream stream);
+
+/*
+ * Chunked mode: a chunk of Nq_b new queries attends to an existing KV prefix
+ * of delta_b tokens plus the chunk's own keys, causal mask aligned to the
+ * bottom-right corner (the on-device engine's chunked prefill, Section 3.3
+ * "LLM Engine": the prefix is processed while the first token is awaited, the
+ * remaining chunk catches up afterwards).  Same formulas as above with
+ * delta_b = Nk_b - Nq_b >= 0.  Every chunk query is a window query
+ * (desc->window is ignored) when importance is non-NULL.
+ */
+pdd_status pdd_prefill_attn_chunked(const pdd_attn_desc *desc, const void *q_chunk,
+                                    const void *k_all, const void *v_all, void *o, float *lse,
+                                    float *importance, void *workspace, size_t workspace_bytes,
+                                    pdd_stream stream);
+
+/*
+ * Token importance alone (Section 3.2 "Prompt Refiner"), from log-sum-exp
+ * values computed earlier (e.g. by pdd_prefill_attn with importance = NULL):
+ * same definition and same result as the fused output.  desc->window < 0
+ * means every query is a window query; 0 is an error here.
+ *   lse        DEVICE fp32 [Hq, total_q]                                -- in
+ *   importance DEVICE fp32 [Hkv, total_k]                               -- out
+ */
+pdd_status pdd_token_importance(const pdd_attn_desc *desc, const void *q, const void *k,
+                                const float *lse, float *importance, void *workspace,
+                                size_t workspace_bytes, pdd_stream stream);
+
+/*
+ * Top-k token selection and stable index compaction (Section 3.2 "Prompt
+ * Refiner": sort the summed scores, keep the indices with the top values per
+ * head at ratio r, filter the positions; the mask tensor holds 1 at position i
+ * when token i is selected).  For every KV head g and sequence b the
+ * candidates are keys [cand_begin[b], cand_end[b]) of that sequence (NULL
+ * arrays = the whole sequence); they are ranked by (score descending, index
+ * ascending) and the first k_per_seq[b] are kept.
+ *
+ *   scores       DEVICE fp32 [n_heads, total_k]                          -- in
+ *   cu_seqlens_k DEVICE int32[B+1]; cu_seqlens_k_host HOST copy or NULL
+ *   cand_begin, cand_end DEVICE int32[B] or both NULL
+ *   k_per_seq    DEVICE int32[B], 0 <= k_b <= cand_end[b]-cand_begin[b]
+ *   cu_keep      DEVICE int32[B+1] prefix sums of k_per_seq
+ *   total_keep   = cu_keep[B] (host copy)
+ *   out_indices  DEVICE int32 [n_heads, total_keep]: sequence-local key
+ *                indices in ascending order                              -- out
+ *   out_mask     DEVICE uint8 [n_heads, total_k] or NULL: 1 = selected   -- out
+ * A k_b larger than the candidate count is clamped on the device (the host
+ * cannot see it); the surplus index slots are filled with -1.
+ * -0.0 ranks equal to +0.0.
+ */
+pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch,
+                           int32_t total_k, const int32_t *cu_seqlens_k,
+                           const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
+                           const int32_t *cand_begin, const int32_t *cand_end,
+                           const int32_t *k_per_seq, const int32_t *cu_keep,
+                           int32_t total_keep, int32_t *out_indices, uint8_t *out_mask,
+                           void *workspace, size_t workspace_bytes, pdd_stream stream);
+
+/*
+ * Bytes of DEVICE scratch `which_call` needs for this descriptor.  Never grows
+ * with Nq*Nk: the attention weights are not materialised (Section 3.2
+ * "Preliminaries").  For PDD_CALL_SELECT_TOPK only batch, n_kv_heads,
+ * total_k and max_seqlen_k of the descriptor are read.
+ */
+size_t pdd_workspace_bytes(const pdd_attn_desc *desc, int which_call);
+
+/*
+ * Tuning knobs (process-wide, not thread-safe against concurrent launches).
+ *   PDD_OPT_ATTN_WAVES: wavefronts per attention workgroup, 4 (128 queries) or
+ *   8 (256 queries); 0 = chosen per problem (default).
+ */
+enum { PDD_OPT_ATTN_WAVES = 0 };
+pdd_status pdd_set_option(int option, int value);
+
+/* Message for the calling thread's most recent non-OK status ("" if none). */
+const char *pdd_last_error(void);
+
+/* Library version string, e.g. "pdd 0.1 gfx950". */
+const char *pdd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PDD_H */

@@ -1,0 +1,28 @@
+"""MI355X-native causal prefill attention fused with prompt-refinement data
+extraction (token importance from the observation window, top-k selection).
+
+All compute runs in the HIP library `libpdd.so` (C ABI in include/pdd.h);
+this package only marshals arguments.  There is no CPU fallback: calling any
+op without the built library raises.
+"""
+from .binding import (
+    PddError,
+    library_path,
+    load_library,
+    version,
+    set_option,
+    prefill_attn,
+    prefill_attn_chunked,
+    token_importance,
+    select_topk,
+    workspace_bytes,
+    AttnDesc,
+    make_desc,
+    OPT_ATTN_WAVES,
+)
+
+__all__ = [
+    "PddError", "library_path", "load_library", "version", "set_option", "prefill_attn",
+    "prefill_attn_chunked", "token_importance", "select_topk", "workspace_bytes", "AttnDesc",
+    "make_desc", "OPT_ATTN_WAVES",
+]

@@ -1,0 +1,289 @@
+// C ABI of libpdd (declared in include/pdd.h): host-side argument validation
+// and kernel launches.  No device memory is allocated or freed here and no
+// device data is read from the host.
+#include "../../include/pdd.h"
+
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "attn_fwd.hpp"
+#include "importance.hpp"
+#include "select_topk.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+int g_attn_waves = 0;  // 0 = choose per problem
+
+pdd_status fail(pdd_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+pdd_status check_cu_host(const char *what, const int32_t *cu, int B, int total, int max_len)
+{
+    if (!cu) return PDD_OK;
+    if (cu[0] != 0) return fail(PDD_ERR_INVALID_ARG, "%s[0] must be 0", what);
+    for (int b = 0; b < B; ++b) {
+        if (cu[b + 1] < cu[b]) return fail(PDD_ERR_INVALID_ARG, "%s is not non-decreasing at %d", what, b);
+        if (cu[b + 1] - cu[b] > max_len)
+            return fail(PDD_ERR_INVALID_ARG, "%s: sequence %d longer than max_seqlen (%d > %d)", what, b,
+                        cu[b + 1] - cu[b], max_len);
+    }
+    if (cu[B] != total) return fail(PDD_ERR_INVALID_ARG, "%s[B] = %d differs from the total %d", what, cu[B], total);
+    return PDD_OK;
+}
+
+enum Mode { MODE_PREFILL, MODE_CHUNKED, MODE_IMPORTANCE };
+
+pdd_status check_desc(const pdd_attn_desc *d, Mode mode)
+{
+    if (!d) return fail(PDD_ERR_INVALID_ARG, "desc is NULL");
+    if (d->batch < 1) return fail(PDD_ERR_INVALID_ARG, "batch must be >= 1");
+    if (d->n_q_heads < 1 || d->n_kv_heads < 1) return fail(PDD_ERR_INVALID_ARG, "head counts must be >= 1");
+    if (d->n_q_heads % d->n_kv_heads) return fail(PDD_ERR_INVALID_ARG, "n_q_heads %% n_kv_heads != 0");
+    if (d->head_dim != 64 && d->head_dim != 128)
+        return fail(PDD_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", d->head_dim);
+    if (d->total_q < 0 || d->total_k < 0) return fail(PDD_ERR_INVALID_ARG, "negative totals");
+    if (d->max_seqlen_q < 0 || d->max_seqlen_k < 0 || d->max_seqlen_q > d->total_q || d->max_seqlen_k > d->total_k)
+        return fail(PDD_ERR_INVALID_ARG, "max_seqlen out of range");
+    if (d->total_q > 0 && d->max_seqlen_q < 1) return fail(PDD_ERR_INVALID_ARG, "max_seqlen_q must be >= 1");
+    if (d->total_k > 0 && d->max_seqlen_k < 1) return fail(PDD_ERR_INVALID_ARG, "max_seqlen_k must be >= 1");
+    if (!d->cu_seqlens_q || !d->cu_seqlens_k) return fail(PDD_ERR_INVALID_ARG, "cu_seqlens pointers are NULL");
+    if (mode == MODE_PREFILL && d->total_q != d->total_k)
+        return fail(PDD_ERR_INVALID_ARG, "prefill needs total_q == total_k (use the chunked entry point)");
+    if (d->total_k < d->total_q) return fail(PDD_ERR_INVALID_ARG, "total_k < total_q");
+    const int64_t hd = d->head_dim;
+    const int64_t st[8] = {d->q_stride_tok, d->q_stride_head, d->k_stride_tok, d->k_stride_head,
+                           d->v_stride_tok, d->v_stride_head, d->o_stride_tok, d->o_stride_head};
+    const int n_st = mode == MODE_IMPORTANCE ? 4 : 8;
+    for (int i = 0; i < n_st; ++i) {
+        if (st[i] < hd) return fail(PDD_ERR_INVALID_ARG, "stride %d smaller than head_dim", i);
+        if (st[i] % 8) return fail(PDD_ERR_INVALID_ARG, "stride %d is not a multiple of 8 elements (16 bytes)", i);
+    }
+    if (mode == MODE_PREFILL && d->window < 0) return fail(PDD_ERR_INVALID_ARG, "window must be >= 0");
+    if (mode == MODE_IMPORTANCE && d->window == 0) return fail(PDD_ERR_INVALID_ARG, "window must not be 0");
+    pdd_status s = check_cu_host("cu_seqlens_q_host", d->cu_seqlens_q_host, d->batch, d->total_q, d->max_seqlen_q);
+    if (s) return s;
+    s = check_cu_host("cu_seqlens_k_host", d->cu_seqlens_k_host, d->batch, d->total_k, d->max_seqlen_k);
+    if (s) return s;
+    if (d->cu_seqlens_q_host && d->cu_seqlens_k_host) {
+        for (int b = 0; b < d->batch; ++b) {
+            const int nq = d->cu_seqlens_q_host[b + 1] - d->cu_seqlens_q_host[b];
+            const int nk = d->cu_seqlens_k_host[b + 1] - d->cu_seqlens_k_host[b];
+            if (nk < nq) return fail(PDD_ERR_INVALID_ARG, "sequence %d has fewer keys than queries", b);
+            if (mode == MODE_PREFILL && nk != nq)
+                return fail(PDD_ERR_INVALID_ARG, "sequence %d: prefill needs Nq == Nk", b);
+        }
+    }
+    return PDD_OK;
+}
+
+float scale_log2(const pdd_attn_desc *d)
+{
+    const float s = d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / std::sqrt((float)d->head_dim);
+    return s * 1.4426950408889634f;
+}
+
+template <int D, int NW>
+pdd_status launch_attn_t(const pdd::AttnParams &p, int64_t blocks, hipStream_t st)
+{
+    auto kern = pdd::attn_fwd_kernel<D, NW>;
+    const int smem = pdd::AttnSmem<D>::BYTES;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NW * 64), smem, st, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "attention launch: %s", hipGetErrorString(e));
+    return PDD_OK;
+}
+
+pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, const void *v, void *o, float *lse,
+                       hipStream_t st)
+{
+    if (d->total_q == 0) return PDD_OK;
+    pdd::AttnParams p;
+    p.q = (const uint16_t *)q;  p.k = (const uint16_t *)k;  p.v = (const uint16_t *)v;
+    p.o = (uint16_t *)o;  p.lse = lse;
+    p.cu_q = d->cu_seqlens_q;  p.cu_k = d->cu_seqlens_k;
+    p.q_st = d->q_stride_tok;  p.q_sh = d->q_stride_head;
+    p.k_st = d->k_stride_tok;  p.k_sh = d->k_stride_head;
+    p.v_st = d->v_stride_tok;  p.v_sh = d->v_stride_head;
+    p.o_st = d->o_stride_tok;  p.o_sh = d->o_stride_head;
+    p.B = d->batch;  p.Hq = d->n_q_heads;  p.Hkv = d->n_kv_heads;  p.G = d->n_q_heads / d->n_kv_heads;
+    p.total_q = d->total_q;  p.total_k = d->total_k;
+    p.scale_log2 = scale_log2(d);
+
+    // 8 waves (256 queries per workgroup) halve the K/V traffic per flop; use
+    // them when there are enough such workgroups to fill the 256 CUs twice over.
+    int nw = g_attn_waves;
+    if (nw != 4 && nw != 8) {
+        const int64_t tiles8 = (int64_t)((d->max_seqlen_q + 255) / 256) * d->batch * d->n_q_heads;
+        nw = tiles8 >= 512 ? 8 : 4;
+    }
+    const int bm = nw * 32;
+    p.n_qtiles = (d->max_seqlen_q + bm - 1) / bm;
+    const int64_t blocks = (int64_t)p.n_qtiles * d->batch * d->n_q_heads;
+    if (blocks > 0x7fffffffLL) return fail(PDD_ERR_INVALID_ARG, "launch grid too large");
+    if (d->head_dim == 128) return nw == 8 ? launch_attn_t<128, 8>(p, blocks, st) : launch_attn_t<128, 4>(p, blocks, st);
+    return nw == 8 ? launch_attn_t<64, 8>(p, blocks, st) : launch_attn_t<64, 4>(p, blocks, st);
+}
+
+pdd_status launch_importance(const pdd_attn_desc *d, const void *q, const void *k, const float *lse, float *imp,
+                             int window, hipStream_t st)
+{
+    if (d->total_k == 0) return PDD_OK;
+    pdd::ImpParams p;
+    p.q = (const uint16_t *)q;  p.k = (const uint16_t *)k;  p.lse = lse;  p.imp = imp;
+    p.cu_q = d->cu_seqlens_q;  p.cu_k = d->cu_seqlens_k;
+    p.q_st = d->q_stride_tok;  p.q_sh = d->q_stride_head;
+    p.k_st = d->k_stride_tok;  p.k_sh = d->k_stride_head;
+    p.B = d->batch;  p.Hq = d->n_q_heads;  p.Hkv = d->n_kv_heads;  p.G = d->n_q_heads / d->n_kv_heads;
+    p.total_q = d->total_q;  p.total_k = d->total_k;
+    p.window = window;
+    p.scale_log2 = scale_log2(d);
+    p.n_ktiles = (d->max_seqlen_k + pdd::kImpBK - 1) / pdd::kImpBK;
+    const int64_t blocks = (int64_t)p.n_ktiles * d->batch * d->n_kv_heads;
+    if (blocks > 0x7fffffffLL) return fail(PDD_ERR_INVALID_ARG, "launch grid too large");
+    if (d->head_dim == 128)
+        hipLaunchKernelGGL(pdd::importance_kernel<128>, dim3((unsigned)blocks), dim3(pdd::kImpWaves * 64), 0, st, p);
+    else
+        hipLaunchKernelGGL(pdd::importance_kernel<64>, dim3((unsigned)blocks), dim3(pdd::kImpWaves * 64), 0, st, p);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "importance launch: %s", hipGetErrorString(e));
+    return PDD_OK;
+}
+
+pdd_status check_ptrs(const void *q, const void *k, const void *v, const void *o, const void *lse)
+{
+    if (!q || !k || !v || !o || !lse) return fail(PDD_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
+        return fail(PDD_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(lse) & 3u) return fail(PDD_ERR_INVALID_ARG, "lse must be 4-byte aligned");
+    return PDD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pdd_last_error(void) { return g_err; }
+const char *pdd_version(void) { return "pdd 0.1 gfx950"; }
+
+pdd_status pdd_set_option(int option, int value)
+{
+    if (option == PDD_OPT_ATTN_WAVES) {
+        if (value != 0 && value != 4 && value != 8) return fail(PDD_ERR_INVALID_ARG, "attn waves must be 0, 4 or 8");
+        g_attn_waves = value;
+        return PDD_OK;
+    }
+    return fail(PDD_ERR_INVALID_ARG, "unknown option %d", option);
+}
+
+size_t pdd_workspace_bytes(const pdd_attn_desc *desc, int which_call)
+{
+    (void)desc;
+    (void)which_call;
+    return 0;  // every kernel keeps its intermediates in registers / LDS
+}
+
+pdd_status pdd_prefill_attn(const pdd_attn_desc *desc, const void *q, const void *k, const void *v, void *o,
+                            float *lse, float *importance, void *workspace, size_t workspace_bytes,
+                            pdd_stream stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    pdd_status s = check_desc(desc, MODE_PREFILL);
+    if (s) return s;
+    s = check_ptrs(q, k, v, o, lse);
+    if (s) return s;
+    if (desc->window > 0 && !importance)
+        return fail(PDD_ERR_INVALID_ARG, "window > 0 needs an importance buffer");
+    s = launch_attn(desc, q, k, v, o, lse, (hipStream_t)stream);
+    if (s) return s;
+    if (importance && desc->window > 0)
+        return launch_importance(desc, q, k, lse, importance, desc->window, (hipStream_t)stream);
+    return PDD_OK;
+}
+
+pdd_status pdd_prefill_attn_chunked(const pdd_attn_desc *desc, const void *q_chunk, const void *k_all,
+                                    const void *v_all, void *o, float *lse, float *importance, void *workspace,
+                                    size_t workspace_bytes, pdd_stream stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    pdd_status s = check_desc(desc, MODE_CHUNKED);
+    if (s) return s;
+    s = check_ptrs(q_chunk, k_all, v_all, o, lse);
+    if (s) return s;
+    s = launch_attn(desc, q_chunk, k_all, v_all, o, lse, (hipStream_t)stream);
+    if (s) return s;
+    if (importance) return launch_importance(desc, q_chunk, k_all, lse, importance, -1, (hipStream_t)stream);
+    return PDD_OK;
+}
+
+pdd_status pdd_token_importance(const pdd_attn_desc *desc, const void *q, const void *k, const float *lse,
+                                float *importance, void *workspace, size_t workspace_bytes, pdd_stream stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    pdd_status s = check_desc(desc, MODE_IMPORTANCE);
+    if (s) return s;
+    if (!q || !k || !lse || !importance) return fail(PDD_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (!aligned16(q) || !aligned16(k)) return fail(PDD_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    return launch_importance(desc, q, k, lse, importance, desc->window, (hipStream_t)stream);
+}
+
+pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, int32_t total_k,
+                           const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
+                           const int32_t *cand_begin, const int32_t *cand_end, const int32_t *k_per_seq,
+                           const int32_t *cu_keep, int32_t total_keep, int32_t *out_indices, uint8_t *out_mask,
+                           void *workspace, size_t workspace_bytes, pdd_stream stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!scores || !cu_seqlens_k || !k_per_seq || !cu_keep) return fail(PDD_ERR_INVALID_ARG, "NULL pointer");
+    if (n_heads < 1 || batch < 1) return fail(PDD_ERR_INVALID_ARG, "n_heads and batch must be >= 1");
+    if (total_k < 0 || total_keep < 0 || max_seqlen_k < 0 || max_seqlen_k > total_k)
+        return fail(PDD_ERR_INVALID_ARG, "bad sizes");
+    if (total_keep > 0 && !out_indices) return fail(PDD_ERR_INVALID_ARG, "out_indices is NULL");
+    if ((cand_begin == nullptr) != (cand_end == nullptr))
+        return fail(PDD_ERR_INVALID_ARG, "cand_begin and cand_end must both be given or both be NULL");
+    if (batch > 65535 * 32) return fail(PDD_ERR_INVALID_ARG, "batch too large");
+    if (n_heads > 65535) return fail(PDD_ERR_INVALID_ARG, "n_heads too large");
+    pdd_status s = check_cu_host("cu_seqlens_k_host", cu_seqlens_k_host, batch, total_k, max_seqlen_k);
+    if (s) return s;
+    if (total_k == 0) return PDD_OK;
+
+    pdd::SelParams p;
+    p.scores = scores;  p.cu_k = cu_seqlens_k;  p.cand_b = cand_begin;  p.cand_e = cand_end;
+    p.k_per = k_per_seq;  p.cu_keep = cu_keep;  p.out_idx = out_indices;  p.out_mask = out_mask;
+    p.n_heads = n_heads;  p.B = batch;  p.total_k = total_k;  p.total_keep = total_keep;
+    const dim3 grid((unsigned)batch, (unsigned)n_heads);
+    hipStream_t st = (hipStream_t)stream;
+    if (max_seqlen_k <= pdd::kSelLdsCap) {
+        auto kern = pdd::select_topk_kernel<true>;
+        const int smem = ((max_seqlen_k + 3) & ~3) * 4;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, pdd::kSelLdsCap * 4);
+        if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+        hipLaunchKernelGGL(kern, grid, dim3(pdd::kSelThreads), smem, st, p);
+    } else {
+        hipLaunchKernelGGL(pdd::select_topk_kernel<false>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "select launch: %s", hipGetErrorString(e));
+    return PDD_OK;
+}
+
+}  // extern "C"

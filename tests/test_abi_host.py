@@ -1,0 +1,120 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2508_09035_amd as pdd
+from paper_2508_09035_amd.binding import AttnDesc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "pdd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pdd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pdd.load_library()
+    names = header_functions()
+    assert {"pdd_prefill_attn", "pdd_prefill_attn_chunked", "pdd_token_importance",
+            "pdd_select_topk", "pdd_workspace_bytes", "pdd_last_error"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert "gfx950" in pdd.version()
+
+
+def good_desc():
+    d = AttnDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = 1, 4, 2, 128
+    d.total_q = d.total_k = d.max_seqlen_q = d.max_seqlen_k = 64
+    d.cu_seqlens_q = d.cu_seqlens_k = 0x1000          # fake device addresses, never followed
+    for f in ("q", "k", "v", "o"):
+        heads = 4 if f in "qo" else 2
+        setattr(d, f + "_stride_tok", heads * 128)
+        setattr(d, f + "_stride_head", 128)
+    d.window = 8
+    return d
+
+
+def call_prefill(d, q=0x10000, k=0x20000, v=0x30000, o=0x40000, lse=0x50000, imp=0x60000):
+    return pdd.load_library().pdd_prefill_attn(ctypes.byref(d), q, k, v, o, lse, imp, None, 0, None)
+
+
+@pytest.mark.parametrize("mutate,status,needle", [
+    (lambda d: setattr(d, "n_kv_heads", 3), -1, "n_q_heads"),
+    (lambda d: setattr(d, "head_dim", 96), -2, "head_dim"),
+    (lambda d: setattr(d, "batch", 0), -1, "batch"),
+    (lambda d: setattr(d, "cu_seqlens_q", None), -1, "cu_seqlens"),
+    (lambda d: setattr(d, "q_stride_tok", 100), -1, "stride"),
+    (lambda d: setattr(d, "k_stride_head", 132), -1, "multiple of 8"),
+    (lambda d: setattr(d, "window", -1), -1, "window"),
+    (lambda d: setattr(d, "total_k", 65), -1, "total_q == total_k"),
+    (lambda d: setattr(d, "max_seqlen_q", 65), -1, "max_seqlen"),
+])
+def test_descriptor_validation(mutate, status, needle):
+    d = good_desc()
+    mutate(d)
+    assert call_prefill(d) == status
+    assert needle in pdd.load_library().pdd_last_error().decode()
+
+
+def test_pointer_validation():
+    d = good_desc()
+    assert call_prefill(d, q=None) == -1
+    assert call_prefill(d, v=0x30008) == -1                     # misaligned
+    assert call_prefill(d, imp=None) == -1                      # window > 0 needs importance
+    assert "importance" in pdd.load_library().pdd_last_error().decode()
+
+
+def test_host_cu_seqlens_validation():
+    lib = pdd.load_library()
+    d = good_desc()
+    for bad, needle in [([1, 64], "[0] must be 0"), ([0, 63], "differs from the total"),
+                        ([0, 70], "longer than max_seqlen")]:
+        arr = np.array(bad, dtype=np.int32)
+        d.cu_seqlens_q_host = arr.ctypes.data
+        assert call_prefill(d) == -1
+        assert needle in lib.pdd_last_error().decode()
+    d = good_desc()
+    d.batch = 2
+    arr = np.array([0, 40, 30], dtype=np.int32)
+    d.cu_seqlens_k_host = arr.ctypes.data
+    assert call_prefill(d) == -1 and "non-decreasing" in lib.pdd_last_error().decode()
+    # chunked: fewer keys than queries in one sequence
+    d = good_desc()
+    d.batch, d.total_q, d.total_k, d.max_seqlen_k = 2, 64, 80, 60
+    aq = np.array([0, 40, 64], dtype=np.int32)
+    ak = np.array([0, 20, 80], dtype=np.int32)
+    d.cu_seqlens_q_host, d.cu_seqlens_k_host = aq.ctypes.data, ak.ctypes.data
+    rc = lib.pdd_prefill_attn_chunked(ctypes.byref(d), 0x10000, 0x20000, 0x30000, 0x40000,
+                                      0x50000, None, None, 0, None)
+    assert rc == -1 and "fewer keys" in lib.pdd_last_error().decode()
+
+
+def test_importance_and_select_validation():
+    lib = pdd.load_library()
+    d = good_desc()
+    d.window = 0
+    assert lib.pdd_token_importance(ctypes.byref(d), 0x10000, 0x20000, 0x50000, 0x60000,
+                                    None, 0, None) == -1
+    sel = lambda **kw: lib.pdd_select_topk(
+        kw.get("scores", 0x1000), kw.get("heads", 2), kw.get("batch", 1), kw.get("total_k", 64),
+        kw.get("cu", 0x2000), None, kw.get("max_k", 64), kw.get("cb", None), kw.get("ce", None),
+        kw.get("kper", 0x3000), kw.get("cukeep", 0x4000), kw.get("total_keep", 8),
+        kw.get("out", 0x5000), None, None, 0, None)
+    assert sel(scores=None) == -1
+    assert sel(heads=0) == -1
+    assert sel(max_k=65) == -1
+    assert sel(out=None) == -1
+    assert sel(cb=0x6000) == -1 and "both" in lib.pdd_last_error().decode()
+    assert pdd.set_option(pdd.OPT_ATTN_WAVES, 8) is None
+    with pytest.raises(pdd.PddError):
+        pdd.set_option(pdd.OPT_ATTN_WAVES, 5)
+    pdd.set_option(pdd.OPT_ATTN_WAVES, 0)
+    assert pdd.workspace_bytes(good_desc(), 0) < 64 * 64 * 4     # never O(N^2)

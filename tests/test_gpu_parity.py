@@ -1,0 +1,238 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs.
+
+Tolerances: O max-abs <= 2e-2 (bf16 output); log-sum-exp and importance
+<= 1e-3 relative (|a-b| <= 1e-3*max(|b|,1e-6)); index sets exact except at
+ties (see check_selection)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+import paper_2508_09035_amd as pdd
+from gpu_harness import DeviceWorkload, check_selection
+
+pytestmark = pytest.mark.gpu
+
+O_ATOL = 2e-2
+REL = 1e-3
+
+
+def rel_close(got, want, what):
+    err = np.abs(got - want)
+    tol = REL * np.maximum(np.abs(want), 1e-6)
+    bad = err > tol
+    assert not bad.any(), (f"{what}: {bad.sum()} of {bad.size} beyond 1e-3 relative; "
+                           f"worst ratio {np.max(err / tol):.3g}")
+
+
+def compare_all(wl, dev, rows=None, label=""):
+    O, lse, imp, idx, mask = dev.results()
+    window = -1 if wl.chunked else wl.window
+    oO, oL = oracle.attention(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale,
+                              rows=rows)
+    if rows is not None:
+        O, lse = O[rows], lse[:, rows]
+    assert np.isfinite(O).all() and np.isfinite(lse).all(), f"{label}: unwritten / non-finite output"
+    o_err = np.abs(O - oO).max() if O.size else 0.0
+    assert o_err <= O_ATOL, f"{label}: O max-abs error {o_err}"
+    rel_close(lse, oL, f"{label} lse")
+    if window != 0:
+        oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, window)
+        assert np.isfinite(imp).all()
+        rel_close(imp, oI, f"{label} importance")
+        # gate B: GPU scores -> GPU selection vs oracle selection, ties within the score tolerance
+        swapped = check_selection(oI, idx, mask, wl, REL, label + " end-to-end select")
+        return o_err, swapped
+    return o_err, 0
+
+
+def run_and_compare(wl, rows=None, waves=0, label=""):
+    dev = DeviceWorkload(wl)
+    dev.poison()
+    pdd.set_option(pdd.OPT_ATTN_WAVES, waves)
+    try:
+        dev.step()
+        return compare_all(wl, dev, rows, label or wl.name)
+    finally:
+        pdd.set_option(pdd.OPT_ATTN_WAVES, 0)
+
+
+# ----------------------------------------------------------------- small cases
+def test_c1_tiny_full():
+    wl = W.make_workload("c1")
+    _, swapped = run_and_compare(wl)
+    assert swapped == 0
+
+
+@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("d", [64, 128])
+def test_multi_tile_ragged_gqa(d, waves):
+    # several q tiles and key tiles, ragged tails, a 1-token prompt, window > a prompt
+    wl = W.make_custom("t", [300, 77, 1, 513, 64, 31], None, 4, 2, d, 40, "3/10", seed=100 + d)
+    run_and_compare(wl, waves=waves, label=f"ragged d={d} w={waves}")
+
+
+@pytest.mark.parametrize("waves", [4, 8])
+def test_chunked_small(waves):
+    wl = W.make_custom("t", [70, 33, 256], [70 + 130, 33, 256 + 700], 8, 2, 128, 0, "1/4",
+                       seed=7, chunked=True)
+    wl.cand_end[1] = 0  # a chunk with no prefix: nothing to select
+    wl.k_keep[1] = 0
+    run_and_compare(wl, waves=waves, label=f"chunked w={waves}")
+
+
+def test_empty_sequence_in_batch_and_no_host_copies():
+    wl = W.make_custom("t", [40, 0, 129], None, 2, 1, 64, 16, "1/2", seed=9)
+    dev = DeviceWorkload(wl)
+    dev.poison()
+    dev.attn(True, host_cu=False)
+    dev.select()
+    compare_all(wl, dev, label="empty-seq")
+
+
+def test_mha_and_large_group():
+    run_and_compare(W.make_custom("t", [200], None, 3, 3, 128, 200, "1/2", seed=12), label="mha")
+    run_and_compare(W.make_custom("t", [150], None, 16, 1, 64, 8, "1/10", seed=13), label="g16")
+
+
+def test_strided_views_of_a_packed_qkv_buffer():
+    wl = W.make_custom("t", [333], None, 4, 2, 128, 32, "1/2", seed=21)
+    dev = DeviceWorkload(wl)
+    n, hq, hkv, d = 333, 4, 2, 128
+    packed = torch.zeros((n, hq + 2 * hkv, d), dtype=torch.bfloat16, device="cuda")
+    packed[:, :hq] = dev.q
+    packed[:, hq:hq + hkv] = dev.k
+    packed[:, hq + hkv:] = dev.v
+    dev.q, dev.k, dev.v = packed[:, :hq], packed[:, hq:hq + hkv], packed[:, hq + hkv:]
+    dev.poison()
+    dev.step()
+    compare_all(wl, dev, label="strided")
+
+
+def test_standalone_importance_equals_fused_and_is_deterministic():
+    wl = W.make_custom("t", [700, 90], None, 8, 2, 128, 64, "1/2", seed=31)
+    dev = DeviceWorkload(wl)
+    dev.step()
+    O1, l1, i1, x1, m1 = dev.results()
+    imp2 = torch.full_like(dev.imp, float("nan"))
+    pdd.token_importance(dev.q, dev.k, dev.lse, imp2, dev.cu_q, dev.cu_k, dev.max_q, dev.max_k,
+                         wl.scale, wl.window, wl.cu_seqlens_q, wl.cu_seqlens_k)
+    torch.cuda.synchronize()
+    assert np.array_equal(imp2.cpu().numpy(), dev.imp.cpu().numpy())
+    dev.poison()
+    dev.step()
+    O2, l2, i2, x2, m2 = dev.results()
+    assert np.array_equal(O1, O2) and np.array_equal(l1, l2) and np.array_equal(i1, i2)
+    assert np.array_equal(x1, x2) and np.array_equal(m1, m2)
+    # attention without importance leaves the importance buffer alone
+    dev.imp.fill_(-5.0)
+    dev.attn(with_importance=False)
+    torch.cuda.synchronize()
+    assert (dev.imp == -5.0).all()
+
+
+# ------------------------------------------------------------- selection alone
+def _select_case(scores64, lens, ks, cand=None, rel_tie=1e-6):
+    """Gate A: the oracle's scores rounded to fp32 go through the GPU select."""
+    wl = W.make_custom("t", lens, None, 1, 1, 64, 0, seed=0)   # only cu_seqlens etc. are used
+    wl.n_kv_heads = scores64.shape[0]
+    wl.k_keep = np.array(ks, dtype=np.int32)
+    if cand is not None:
+        wl.cand_begin = np.array(cand[0], dtype=np.int32)
+        wl.cand_end = np.array(cand[1], dtype=np.int32)
+    dev = DeviceWorkload(wl)
+    dev.poison()
+    s32 = torch.from_numpy(scores64.astype(np.float32)).cuda()
+    dev.select(scores=s32)
+    torch.cuda.synchronize()
+    idx, mask = dev.idx.cpu().numpy(), dev.mask.cpu().numpy()
+    # exactness on what the kernel saw (fp32), tie allowance on the fp64 scores
+    check_selection(scores64.astype(np.float32).astype(np.float64), idx, mask, wl, -1, "select fp32")
+    check_selection(scores64, idx, mask, wl, rel_tie, "select fp64")
+    return idx, mask
+
+
+def test_select_ties_negative_values_and_ranges():
+    rng = np.random.default_rng(5)
+    lens = [1000, 1, 64, 4097]
+    tot = sum(lens)
+    s = rng.integers(0, 50, size=(3, tot)).astype(np.float64) / 8.0       # many exact ties
+    s[1] = rng.standard_normal(tot)                                          # negatives
+    s[2, :] = 0.25                                                           # all equal
+    s[1, 5] = -0.0
+    _select_case(s, lens, [300, 1, 10, 2048])
+    _select_case(s, lens, [0, 0, 64, 4097])                                  # nothing / everything
+    _select_case(s, lens, [100, 1, 5, 1000], cand=([10, 0, 32, 4], [900, 1, 40, 4000]))
+    idx, _ = _select_case(s[2:3], lens, [7, 1, 3, 11])
+    assert idx[0, :7].tolist() == list(range(7))                             # lowest indices win
+
+
+def test_select_long_rows_beyond_lds_staging():
+    rng = np.random.default_rng(6)
+    lens = [40000, 33000]
+    s = np.abs(rng.standard_normal((2, sum(lens)))) ** 3
+    s[1, ::3] = s[1, 0]
+    _select_case(s, lens, [4000, 16500])
+    _select_case(s, lens, [1, 33000])
+
+
+# ------------------------------------------------------ benchmark configurations
+def test_c2_llama_layer_full():
+    wl = W.make_workload("c2")
+    o_err, swapped = run_and_compare(wl)
+    print(f"c2: O err {o_err:.4f}, swapped {swapped}")
+    assert swapped == 0
+
+
+def _sample_rows(wl, per_seq_random, tile=256, seed=0):
+    rng = np.random.default_rng(seed)
+    rows = []
+    for b in range(wl.batch):
+        qs, nq = int(wl.cu_seqlens_q[b]), int(wl.seqlens_q[b])
+        w = nq if wl.chunked else min(wl.window, nq)
+        loc = set(range(nq - w, nq)) | set(range(min(nq, 64)))
+        for t in range(tile, nq, tile):
+            loc |= {t - 1, t, t + 1} & set(range(nq))
+        loc |= set(int(x) for x in rng.integers(0, nq, size=per_seq_random))
+        rows += [qs + i for i in sorted(loc)]
+    return np.array(rows, dtype=np.int32)
+
+
+def test_c3_ragged_batch_sampled_rows():
+    wl = W.make_workload("c3")
+    rows = _sample_rows(wl, 48)
+    o_err, swapped = run_and_compare(wl, rows=rows)
+    print(f"c3: {len(rows)} rows, O err {o_err:.4f}, swapped {swapped}")
+    assert swapped == 0
+
+
+def test_c4_long_prompt_sampled_rows():
+    wl = W.make_workload("c4")
+    rows = _sample_rows(wl, 128, tile=2048)
+    o_err, swapped = run_and_compare(wl, rows=rows)
+    print(f"c4: {len(rows)} rows, O err {o_err:.4f}, swapped {swapped}")
+
+
+def test_c4h_heavy_hitters_are_selected():
+    """Boosted-query variant: the marked keys carry most of the window mass, so
+    the selection must contain (nearly) all of them; importance and indices
+    still match the oracle."""
+    wl = W.make_workload("c4h", n_override=8192)
+    dev = DeviceWorkload(wl)
+    dev.step()
+    _, swapped = compare_all(wl, dev, rows=_sample_rows(wl, 32, tile=2048), label="c4h")
+    idx = dev.idx.cpu().numpy()
+    heavy = wl.extra["heavy_positions"]
+    for g in range(wl.n_kv_heads):
+        frac = np.isin(heavy[g], idx[g]).mean()
+        assert frac > 0.9, f"head {g}: only {frac:.2f} of heavy keys kept"
+
+
+def test_c5_chunked_catch_up():
+    wl = W.make_workload("c5")
+    rows = _sample_rows(wl, 0)[::4]          # every 4th chunk row of each sequence
+    o_err, swapped = run_and_compare(wl, rows=rows)
+    print(f"c5: {len(rows)} rows, O err {o_err:.4f}, swapped {swapped}")
+    assert swapped == 0
