@@ -269,6 +269,7 @@ pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, 
     p.scores = scores;  p.cu_k = cu_seqlens_k;  p.cand_b = cand_begin;  p.cand_e = cand_end;
     p.k_per = k_per_seq;  p.cu_keep = cu_keep;  p.out_idx = out_indices;  p.out_mask = out_mask;
     p.n_heads = n_heads;  p.B = batch;  p.total_k = total_k;  p.total_keep = total_keep;
+    p.lds_cap = (max_seqlen_k + 3) & ~3;
     const dim3 grid((unsigned)batch, (unsigned)n_heads);
     hipStream_t st = (hipStream_t)stream;
     if (max_seqlen_k <= pdd::kSelLdsCap) {

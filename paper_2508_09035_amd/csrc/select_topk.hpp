@@ -21,6 +21,7 @@ struct SelParams {
     int32_t *out_idx;
     uint8_t *out_mask;
     int32_t n_heads, B, total_k, total_keep;
+    int32_t lds_cap;   // scores staged per row (STAGED variant): longer rows are truncated
 };
 
 constexpr int kSelThreads = 1024;
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
     int c1 = p.cand_e ? p.cand_e[b] : nk;
     c0 = min(max(c0, 0), nk);
     c1 = min(max(c1, c0), nk);
-    const int n = c1 - c0;
+    const int n = STAGED ? min(c1 - c0, p.lds_cap) : c1 - c0;
     const int keep0 = min(max(p.cu_keep[b], 0), p.total_keep);
     const int keep1 = min(max(p.cu_keep[b + 1], keep0), p.total_keep);
     const int slots = keep1 - keep0;
