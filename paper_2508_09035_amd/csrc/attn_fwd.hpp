@@ -55,6 +55,14 @@ struct AttnSmem {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    // v_max3_f32; inputs are never NaN here, so no canonicalisation is needed
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __device__ __forceinline__ float xchg_half(float x)
 {
     // value held by the lane 32 positions away
@@ -193,6 +201,9 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
         store_tile(0);
     }
     __syncthreads();
+    // Everything loaded so far (Q fragments included) has landed: say so, or the
+    // compiler re-waits for the Q loads inside the loop, behind the prefetches.
+    __builtin_amdgcn_s_waitcnt(0);
 
     for (int it = 0; it < n_tiles; ++it) {
         const int buf = it & 1;
@@ -233,12 +244,12 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
                 }
             }
             // ---- online softmax
-            float tmax = s0[0];
+            float tmax = max3(s0[0], s0[1], s0[2]);
 #pragma unroll
-            for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, s0[e]);
+            for (int e = 3; e < 15; e += 2) tmax = max3(tmax, s0[e], s0[e + 1]);
 #pragma unroll
-            for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s1[e]);
-            tmax = fmaxf(tmax, xchg_half(tmax));
+            for (int e = 0; e < 16; e += 2) tmax = max3(tmax, s1[e], s1[e + 1]);
+            tmax = max3(tmax, s0[15], xchg_half(max3(tmax, s0[15], s0[15])));
             const float m_new = fmaxf(m_run, tmax);
             if (__any(m_new > m_run)) {           // wave-uniform: rescale only when a max moved
                 const float alpha = (m_run == -INFINITY) ? 0.f : fast_exp2((m_run - m_new) * c2);

@@ -10,6 +10,7 @@
 #include <cstring>
 
 #include "attn_fwd.hpp"
+#include "attn_fwd_d128.hpp"
 #include "importance.hpp"
 #include "select_topk.hpp"
 
@@ -94,18 +95,26 @@ float scale_log2(const pdd_attn_desc *d)
     return s * 1.4426950408889634f;
 }
 
-template <int D, int NW>
-pdd_status launch_attn_t(const pdd::AttnParams &p, int64_t blocks, hipStream_t st)
+template <typename Kern>
+pdd_status launch_attn_kernel(Kern kern, int smem, int threads, const pdd::AttnParams &p, int64_t blocks,
+                              hipStream_t st)
 {
-    auto kern = pdd::attn_fwd_kernel<D, NW>;
-    const int smem = pdd::AttnSmem<D>::BYTES;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NW * 64), smem, st, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), smem, st, p);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(PDD_ERR_HIP, "attention launch: %s", hipGetErrorString(e));
     return PDD_OK;
+}
+
+template <int D, int NW>
+pdd_status launch_attn_t(const pdd::AttnParams &p, int64_t blocks, hipStream_t st)
+{
+    if constexpr (D == 128)
+        return launch_attn_kernel(pdd::attn_fwd_d128_kernel<NW>, pdd::kAttn128Smem, NW * 64, p, blocks, st);
+    else
+        return launch_attn_kernel(pdd::attn_fwd_kernel<D, NW>, pdd::AttnSmem<D>::BYTES, NW * 64, p, blocks, st);
 }
 
 pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, const void *v, void *o, float *lse,
