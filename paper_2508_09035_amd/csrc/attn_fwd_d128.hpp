@@ -18,6 +18,7 @@
 //     tile j follow.
 #pragma once
 #include "attn_fwd.hpp"
+#include <type_traits>
 
 namespace pdd {
 
@@ -25,11 +26,42 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 constexpr int kTileBytes = kBN * 256;   // one K or V tile in LDS
-constexpr int kAttn128Smem = 4 * kTileBytes;
+constexpr int kAttn128Bufs = 3;          // K and V tiles are triple buffered
+constexpr int kAttn128Smem = 2 * kAttn128Bufs * kTileBytes;
 
 __device__ __forceinline__ int swz16(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-typedef __attribute__((address_space(3))) void *lds_ptr_t;
+typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
+
+// Raw buffer descriptor (base, num_records in bytes, untyped dword access) held in SGPRs.
+__device__ __forceinline__ i32x4 make_rsrc(const void *base, uint32_t bytes)
+{
+    const uint64_t a = (uint64_t)base;
+    i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int32_t)(uint32_t)a);
+    r.y = __builtin_amdgcn_readfirstlane((int32_t)((uint32_t)(a >> 32) & 0xffffu));
+    r.z = __builtin_amdgcn_readfirstlane((int32_t)bytes);
+    r.w = 0x00020000;
+    return r;
+}
+
+// 16 bytes per lane from the buffer straight into LDS at lds_addr + 16 * lane
+// (lds_addr wave-uniform).  Out-of-range lanes write zeros.  Written as inline
+// assembly so that the transfer stays asynchronous: completion is awaited with
+// an explicit s_waitcnt vmcnt(0) before the workgroup barrier that publishes
+// the tile.  Nothing else in this kernel relies on M0.
+__device__ __forceinline__ void dma16_to_lds(i32x4 rsrc, uint32_t lds_addr, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t *)p;
+}
 
 __device__ __forceinline__ bf16x8 lds_read_tr8(const uint8_t *lo, const uint8_t *hi)
 {
@@ -51,8 +83,8 @@ void attn_fwd_d128_kernel(const AttnParams p)
     constexpr int NLD = 16 / NWAVES;     // buffer_load..lds instructions per tile per wave
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem128[];
-    uint8_t *Ks = smem128;                    // [2][kTileBytes]
-    uint8_t *Vs = smem128 + 2 * kTileBytes;   // [2][kTileBytes]
+    uint8_t *Ks = smem128;                               // [3][kTileBytes], tile t in buffer t % 3
+    uint8_t *Vs = smem128 + kAttn128Bufs * kTileBytes;   // [3][kTileBytes]
 
     int bid = blockIdx.x;
     const int g = bid % p.Hkv;  bid /= p.Hkv;
@@ -96,8 +128,8 @@ void attn_fwd_d128_kernel(const AttnParams p)
     const uint32_t k_row_bytes = (uint32_t)p.k_st * 2u, v_row_bytes = (uint32_t)p.v_st * 2u;
     const uint32_t k_span = nk > 0 ? (uint32_t)(nk - 1) * k_row_bytes + 256u : 0u;
     const uint32_t v_span = nk > 0 ? (uint32_t)(nk - 1) * v_row_bytes + 256u : 0u;
-    const __amdgpu_buffer_rsrc_t rsK = __builtin_amdgcn_make_buffer_rsrc((void *)kbase, 0, (int)k_span, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsV = __builtin_amdgcn_make_buffer_rsrc((void *)vbase, 0, (int)v_span, 0x00020000);
+    const i32x4 rsK = make_rsrc(kbase, k_span), rsV = make_rsrc(vbase, v_span);
+    const uint32_t ks_lds = lds_addr_of(Ks), vs_lds = lds_addr_of(Vs);
 
     // DMA lane mapping: instruction ci of wave w fills LDS rows 4q..4q+3, q = w + NWAVES*ci;
     // lane -> row 4q + lane/16, chunk position lane%16, which holds chunk pos ^ swz(row).
@@ -109,22 +141,18 @@ void attn_fwd_d128_kernel(const AttnParams p)
         kvoff[ci] = (uint32_t)r * k_row_bytes + (uint32_t)c * 16u;
         vvoff[ci] = (uint32_t)r * v_row_bytes + (uint32_t)c * 16u;
     }
-    auto issue_k = [&](int tile) {
-        uint8_t *dst = Ks + (tile & 1) * kTileBytes;
+    auto issue_k = [&](int tile, int buf) {
         // the tile offset goes into the per-lane offset: only that one is range checked
         const uint32_t so = (uint32_t)tile * kBN * k_row_bytes;
 #pragma unroll
         for (int ci = 0; ci < NLD; ++ci)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsK, (lds_ptr_t)(dst + 1024 * (wave + NWAVES * ci)), 16,
-                                                     kvoff[ci] + so, 0, 0, 0);
+            dma16_to_lds(rsK, ks_lds + buf * kTileBytes + 1024 * (wave + NWAVES * ci), kvoff[ci] + so);
     };
-    auto issue_v = [&](int tile) {
-        uint8_t *dst = Vs + (tile & 1) * kTileBytes;
+    auto issue_v = [&](int tile, int buf) {
         const uint32_t so = (uint32_t)tile * kBN * v_row_bytes;
 #pragma unroll
         for (int ci = 0; ci < NLD; ++ci)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsV, (lds_ptr_t)(dst + 1024 * (wave + NWAVES * ci)), 16,
-                                                     vvoff[ci] + so, 0, 0, 0);
+            dma16_to_lds(rsV, vs_lds + buf * kTileBytes + 1024 * (wave + NWAVES * ci), vvoff[ci] + so);
     };
 
     // ---- LDS read addresses (bytes inside a tile)
@@ -156,106 +184,138 @@ void attn_fwd_d128_kernel(const AttnParams p)
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
     const float c2 = p.scale_log2;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    auto qk_tile = [&](int tile, f32x16 &s0, f32x16 &s1) {
-        const uint8_t *kb = Ks + (tile & 1) * kTileBytes;
-        const bool blk1 = tile * kBN + 32 <= wave_lim_max;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { s0[e] = 0.f; s1[e] = 0.f; }
+    // S^T of the 32-key block at byte offset `koff` of the K buffers
+    auto qk_block = [&](uint32_t koff, f32x16 &s) {
+        const uint8_t *kb = Ks + koff;
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
             const bf16x8 a = *(const bf16x8 *)(kb + kaddr[kk]);
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s0, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], kk == 0 ? zero16 : s, 0, 0, 0);
         }
-        if (blk1) {
+    };
+
+    auto row_max = [&](const f32x16 &s) {
+        float tmax = max3(s[0], s[1], s[2]);
 #pragma unroll
-            for (int kk = 0; kk < NKK; ++kk) {
-                const bf16x8 a = *(const bf16x8 *)(kb + 32 * 256 + kaddr[kk]);
-                s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s1, 0, 0, 0);
+        for (int e = 3; e < 15; e += 2) tmax = max3(tmax, s[e], s[e + 1]);
+        tmax = fmaxf(tmax, s[15]);
+        return fmaxf(tmax, xchg_half(tmax));
+    };
+
+    auto rescale = [&](float m_new) {
+        const float alpha = (m_run == -INFINITY) ? 0.f : fast_exp2((m_run - m_new) * c2);
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+        m_run = m_new;
+    };
+
+    auto exp_block = [&](f32x16 &s, float mc) {
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            s[e] = fast_exp2(fmaf(s[e], c2, -mc));
+            psum += s[e];
+        }
+        l_run += psum;
+    };
+
+    // O^T += V^T P^T for the 32-key block at byte offset `voff` of the V buffers
+    auto pv_block = [&](uint32_t voff, const f32x16 &s) {
+        const uint8_t *vb = Vs + voff;
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            f32x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = s[8 * st + e];
+            const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                const bf16x8 a = lds_read_tr8(vb + 4096 * st + vaddr[db][0], vb + 4096 * st + vaddr[db][1]);
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
             }
         }
     };
 
     if (n_tiles > 0) {
-        issue_k(0);
-        issue_v(0);
-        if (n_tiles > 1) issue_k(1);
+        issue_k(0, 0);
+        issue_v(0, 0);
+        if (n_tiles > 1) issue_k(1, 1);
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    f32x16 s0, s1;
-    if (n_tiles > 0) qk_tile(0, s0, s1);   // tile 0 is visible to every wave
+    // Scores are pipelined per 32-key block u = 2*tile + blk: while block u goes
+    // through softmax and PV, the MFMAs of block u+1 are already issued.  Tile t
+    // lives in LDS buffer t % 3; at every tile boundary the current block is in sA.
+    const int n_blocks = 2 * n_tiles;
+    f32x16 sA = zero16, sB = zero16;
+    if (n_tiles > 0) qk_block(0, sA);   // block 0 is visible to every wave
 
-    for (int it = 0; it < n_tiles; ++it) {
-        const int j0 = it * kBN;
+    // ---- hot loop: tiles that no wave of the workgroup has to mask and whose
+    // successor is fully visible to all of them: no per-wave branches at all.
+    //   need: 64 (t+2) - 1 <= m0 + delta  (first query of the workgroup)
+    const int first_lim = m0 + delta;
+    int n_hot = (first_lim + 1) / kBN - 1;           // tiles 0 .. n_hot-1 qualify
+    n_hot = max(0, min(n_hot, n_tiles - 1));
+    n_hot -= n_hot % 3;
+
+    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, uint32_t k_next, uint32_t v_cur) {
+        const float m_new = fmaxf(m_run, row_max(cur));
+        if (__any(m_new > m_run)) rescale(m_new);
+        const float mc = m_run * c2;
+        qk_block(k_next, nxt);
+        exp_block(cur, mc);
+        pv_block(v_cur, cur);
+    };
+    auto hot_tile = [&](auto par_c, const int it) {
+        constexpr int PAR = decltype(par_c)::value;
+        constexpr int P1 = (PAR + 1) % 3, P2 = (PAR + 2) % 3;
+        issue_v(it + 1, P1);
+        if (it + 2 < n_tiles) issue_k(it + 2, P2);
+        hot_half(sA, sB, PAR * kTileBytes + 32 * 256, PAR * kTileBytes);
+        hot_half(sB, sA, P1 * kTileBytes, PAR * kTileBytes + 2 * 4096);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
+    int it = 0;
+    for (; it < n_hot; it += 3) {
+        hot_tile(std::integral_constant<int, 0>{}, it);
+        hot_tile(std::integral_constant<int, 1>{}, it + 1);
+        hot_tile(std::integral_constant<int, 2>{}, it + 2);
+    }
+
+    // ---- remaining tiles (the diagonal region): per-wave activity and masking
+    auto slow_half = [&](f32x16 &cur, f32x16 &nxt, const int u, uint32_t k_next, uint32_t v_cur) {
+        const int j0 = 32 * u;
         const bool cur_active = j0 <= wave_lim_max;
-        const bool nxt_active = it + 1 < n_tiles && j0 + kBN <= wave_lim_max;
-        // the buffers these tiles land in were last read one iteration ago
-        if (it + 1 < n_tiles) issue_v(it + 1);
-        if (it + 2 < n_tiles) issue_k(it + 2);
-
-        f32x16 t0 = s0, t1 = s1;
-        if (nxt_active) qk_tile(it + 1, t0, t1);
-
+        const bool nxt_active = u + 1 < n_blocks && j0 + 32 <= wave_lim_max;
+        if (nxt_active) qk_block(k_next, nxt);
         if (cur_active) {
-            const bool blk1 = (j0 + 32 <= wave_lim_max);
-            if (j0 + kBN - 1 > wave_lim_min) {
+            if (j0 + 31 > wave_lim_min) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int j = j0 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    if (j > lim) s0[e] = -INFINITY;
-                    if (j + 32 > lim) s1[e] = -INFINITY;
+                    if (j > lim) cur[e] = -INFINITY;
                 }
             }
-            float tmax = max3(s0[0], s0[1], s0[2]);
-#pragma unroll
-            for (int e = 3; e < 15; e += 2) tmax = max3(tmax, s0[e], s0[e + 1]);
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) tmax = max3(tmax, s1[e], s1[e + 1]);
-            tmax = fmaxf(tmax, s0[15]);
-            tmax = fmaxf(tmax, xchg_half(tmax));
-            const float m_new = fmaxf(m_run, tmax);
-            if (__any(m_new > m_run)) {
-                const float alpha = (m_run == -INFINITY) ? 0.f : fast_exp2((m_run - m_new) * c2);
-                l_run *= alpha;
-#pragma unroll
-                for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-                m_run = m_new;
-            }
+            const float m_new = fmaxf(m_run, row_max(cur));
+            if (__any(m_new > m_run)) rescale(m_new);
             const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
-            float psum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                s0[e] = fast_exp2(fmaf(s0[e], c2, -mc));
-                psum += s0[e];
-            }
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                s1[e] = fast_exp2(fmaf(s1[e], c2, -mc));
-                psum += s1[e];
-            }
-            l_run += psum;
-
-            const uint8_t *vb = Vs + (it & 1) * kTileBytes;
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                if (st >= 2 && !blk1) break;
-                f32x8 pf;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = (st < 2) ? s0[8 * (st & 1) + e] : s1[8 * (st & 1) + e];
-                const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
-#pragma unroll
-                for (int db = 0; db < NDB; ++db) {
-                    const bf16x8 a = lds_read_tr8(vb + 4096 * st + vaddr[db][0], vb + 4096 * st + vaddr[db][1]);
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
-                }
-            }
+            exp_block(cur, mc);
+            pv_block(v_cur, cur);
         }
-        s0 = t0;
-        s1 = t1;
+    };
+    for (; it < n_tiles; ++it) {
+        const uint32_t b0 = (uint32_t)(it % 3) * kTileBytes, b1 = (uint32_t)((it + 1) % 3) * kTileBytes;
+        if (it + 1 < n_tiles) issue_v(it + 1, (it + 1) % 3);
+        if (it + 2 < n_tiles) issue_k(it + 2, (it + 2) % 3);
+        slow_half(sA, sB, 2 * it, b0 + 32 * 256, b0);
+        slow_half(sB, sA, 2 * it + 1, b1, b0 + 2 * 4096);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
