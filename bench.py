@@ -34,7 +34,7 @@ def time_gpu(fn, iters, warmup):
     return start.elapsed_time(stop) / iters     # ms
 
 
-def cpu_baseline(wl, budget_gflop=60.0):
+def cpu_baseline(wl, budget_gflop=200.0):
     """Time the oracle (as it stands) on a bounded seeded sample of query rows
     of the same workload, on the host cores."""
     import numpy as np
@@ -118,7 +118,8 @@ def main():
         "legs_ms": {"attention": round(ms_attn, 4), "attention+importance": round(ms_attn_imp, 4),
                     "select+compaction": round(ms_select, 4)},
         "select_GBps": round(sel_bytes / (ms_select * 1e-3) / 1e9, 2),
-        "roofline": {"bound": "mfma", "kernel": "attn_fwd_kernel",
+        "roofline": {"bound": "mfma",
+                     "kernel": "attn_fwd_d128_kernel" if wl.head_dim == 128 else "attn_fwd_kernel",
                      "achieved": round(tflops_attn, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 4),
                      "traffic": None},

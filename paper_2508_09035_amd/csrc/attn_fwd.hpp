@@ -65,8 +65,10 @@ __device__ __forceinline__ float max3(float a, float b, float c)
 
 __device__ __forceinline__ float xchg_half(float x)
 {
-    // value held by the lane 32 positions away
-    return __shfl_xor(x, 32, 64);
+    // value held by the lane 32 positions away (v_permlane32_swap: one VALU op, no LDS)
+    const uint32_t u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
 template <int D, int NWAVES>

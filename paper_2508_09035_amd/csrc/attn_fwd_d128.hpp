@@ -264,29 +264,35 @@ void attn_fwd_d128_kernel(const AttnParams p)
     n_hot = max(0, min(n_hot, n_tiles - 1));
     n_hot -= n_hot % 3;
 
-    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, uint32_t k_next, uint32_t v_cur) {
-        const float m_new = fmaxf(m_run, row_max(cur));
+    // `m_cand` carries the row max of `cur` (computed one block earlier, while the
+    // previous PV MFMAs were running) so that the exponentials never wait for a max.
+    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, float &m_cand, uint32_t k_next, uint32_t v_cur) {
+        const float m_new = fmaxf(m_run, m_cand);
         if (__any(m_new > m_run)) rescale(m_new);
         const float mc = m_run * c2;
         qk_block(k_next, nxt);
         exp_block(cur, mc);
         pv_block(v_cur, cur);
+        m_cand = row_max(nxt);
     };
-    auto hot_tile = [&](auto par_c, const int it) {
+    auto hot_tile = [&](auto par_c, const int it, float &m_cand) {
         constexpr int PAR = decltype(par_c)::value;
         constexpr int P1 = (PAR + 1) % 3, P2 = (PAR + 2) % 3;
         issue_v(it + 1, P1);
         if (it + 2 < n_tiles) issue_k(it + 2, P2);
-        hot_half(sA, sB, PAR * kTileBytes + 32 * 256, PAR * kTileBytes);
-        hot_half(sB, sA, P1 * kTileBytes, PAR * kTileBytes + 2 * 4096);
+        hot_half(sA, sB, m_cand, PAR * kTileBytes + 32 * 256, PAR * kTileBytes);
+        hot_half(sB, sA, m_cand, P1 * kTileBytes, PAR * kTileBytes + 2 * 4096);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };
     int it = 0;
-    for (; it < n_hot; it += 3) {
-        hot_tile(std::integral_constant<int, 0>{}, it);
-        hot_tile(std::integral_constant<int, 1>{}, it + 1);
-        hot_tile(std::integral_constant<int, 2>{}, it + 2);
+    if (n_hot > 0) {
+        float m_cand = row_max(sA);
+        for (; it < n_hot; it += 3) {
+            hot_tile(std::integral_constant<int, 0>{}, it, m_cand);
+            hot_tile(std::integral_constant<int, 1>{}, it + 1, m_cand);
+            hot_tile(std::integral_constant<int, 2>{}, it + 2, m_cand);
+        }
     }
 
     // ---- remaining tiles (the diagonal region): per-wave activity and masking
