@@ -7,13 +7,18 @@
 //
 // The final log-sum-exp of every window row is an input, so each probability
 // is recomputed from one QK^T tile and added into a per-key column sum; the
-// attention matrix is never stored.  Work is split over KEYS: a wave owns 32
-// keys, keeps their K fragments in registers (B operand) and sweeps all window
-// rows of all G query heads (A operand, streamed from L2).  S = Q K^T puts key
-// (l % 32) in lane l and 16 query rows in its accumulator registers, so the
-// sum over queries is in-lane; no atomics, fixed summation order.
+// attention matrix is never stored.  Work is split over KEYS: a workgroup of 4
+// waves owns 256 keys, each wave 64 of them (two 32-key groups whose K
+// fragments stay in registers as B operands for the whole kernel).  The window
+// rows of the G query heads are streamed through LDS in blocks of 32 rows
+// (buffer_load ... lds, double buffered, swizzled like the attention K tile)
+// together with their log-sum-exp values, so every Q fragment read from LDS
+// feeds two MFMAs and every Q row is fetched from L2 once per workgroup.
+// S = Q K^T puts key (l % 32) in lane l and 16 query rows in its accumulator
+// registers, so the sum over queries is in-lane; no atomics, fixed summation
+// order, deterministic.
 #pragma once
-#include "attn_fwd.hpp"
+#include "attn_fwd_d128.hpp"
 
 namespace pdd {
 
@@ -29,12 +34,20 @@ struct ImpParams {
 };
 
 constexpr int kImpWaves = 4;
-constexpr int kImpBK = 32 * kImpWaves;  // keys per workgroup
+constexpr int kImpBK = 64 * kImpWaves;  // keys per workgroup
 
 template <int D>
 __global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpParams p)
 {
+#if defined(__HIP_DEVICE_COMPILE__)
     constexpr int NKK = D / 16;
+    constexpr int ROW_BYTES = D * 2;             // one Q row in LDS
+    constexpr int CH = D / 8;                    // 16-byte chunks per row
+    constexpr int QBLK_BYTES = 32 * ROW_BYTES;   // one block of 32 query rows
+    constexpr int NLD = QBLK_BYTES / (kImpWaves * 1024);   // DMA instructions per block per wave (2 or 1)
+    __shared__ __attribute__((aligned(1024))) uint8_t qs_lds[2][QBLK_BYTES];
+    __shared__ __attribute__((aligned(16))) float lse_lds[2][32];
+
     int bid = blockIdx.x;
     const int g = bid % p.Hkv;  bid /= p.Hkv;
     const int b = bid % p.B;    bid /= p.B;
@@ -43,58 +56,132 @@ __global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpPar
     const int qs = min(p.cu_q[b], p.total_q), qe = min(p.cu_q[b + 1], p.total_q);
     const int ks = min(p.cu_k[b], p.total_k), ke = min(p.cu_k[b + 1], p.total_k);
     const int nq = qe - qs, nk = ke - ks;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j_wg0 = kt * kImpBK;
+    if (j_wg0 >= nk) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hh = lane >> 5;
-    const int jw0 = kt * kImpBK + 32 * wave;   // first key of this wave
-    if (jw0 >= nk) return;
-    const int j = jw0 + n;
     const int delta = nk - nq;
     const int W = (p.window < 0 || p.window > nq) ? nq : p.window;
-    const int iw0 = nq - W;                    // first window row
+    const int iw0 = nq - W;                       // first window row
+    const int jw0 = j_wg0 + 64 * wave;            // first key of this wave
 
-    // K fragments (B operand): key j, dims 16*kk + 8*hh .. +7
-    bf16x8 kf[NKK];
-    {
-        const uint16_t *kp = p.k + (int64_t)(ks + min(j, nk - 1)) * p.k_st + (int64_t)g * p.k_sh + 8 * hh;
+    // K fragments (B operand) of the wave's two 32-key groups: key j, dims 16 kk + 8 hh .. +7
+    bf16x8 kf[2][NKK];
+    int jkey[2];
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) kf[kk] = *(const bf16x8 *)(kp + 16 * kk);
+    for (int kg = 0; kg < 2; ++kg) {
+        jkey[kg] = jw0 + 32 * kg + n;
+        const uint16_t *kp = p.k + (int64_t)(ks + min(jkey[kg], nk - 1)) * p.k_st + (int64_t)g * p.k_sh + 8 * hh;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) kf[kg][kk] = *(const bf16x8 *)(kp + 16 * kk);
     }
     const float c2 = p.scale_log2;
     constexpr float kLog2e = 1.4426950408889634f;
-    float colsum = 0.f;
+    float colsum[2] = {0.f, 0.f};
 
-    if (nq > 0 && delta >= 0) {
-        // first row block that can see key jw0: rows i >= jw0 - delta
-        const int rb_first = max(0, (jw0 - delta - iw0) / 32);
+    if (nq > 0 && delta >= 0 && W > 0) {
+        // row blocks: (head in group, 32-row block of the window); blocks whose rows all lie
+        // before key j_wg0 - delta see none of this workgroup's keys and are skipped
         const int n_rb = (W + 31) / 32;
-        for (int hg = 0; hg < p.G; ++hg) {
-            const int h = g * p.G + hg;
-            const float *lse_h = p.lse + (int64_t)h * p.total_q + qs;
-            for (int rb = rb_first; rb < n_rb; ++rb) {
-                const int i0 = iw0 + 32 * rb;
-                const int irow = min(i0 + n, nq - 1);   // A operand row of this lane
-                const uint16_t *qp = p.q + (int64_t)(qs + irow) * p.q_st + (int64_t)h * p.q_sh + 8 * hh;
-                f32x16 s;
+        const int rb_first = min(n_rb, max(0, (j_wg0 - delta - iw0) / 32));
+        const int n_items = p.G * (n_rb - rb_first);
+
+        // Q rows of this sequence, all heads: buffer descriptor spanning the whole sequence
+        const uint16_t *qbase = p.q + (int64_t)qs * p.q_st;
+        const uint32_t q_row_bytes = (uint32_t)p.q_st * 2u;
+        const uint32_t q_span = (uint32_t)(nq - 1) * q_row_bytes + (uint32_t)p.Hq * (uint32_t)p.q_sh * 2u;
+        const i32x4 rsQ = make_rsrc(qbase, q_span);
+        const uint32_t q_lds = lds_addr_of(&qs_lds[0][0]);
+        // lane -> (row in block, chunk position); LDS chunk position holds chunk pos ^ swizzle(row)
+        uint32_t qvoff[NLD];
+        int qrow_l[NLD];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) s[e] = 0.f;
+        for (int ci = 0; ci < NLD; ++ci) {
+            const int flat = (wave + kImpWaves * ci) * 64 + lane;          // 16-byte slot in the block
+            const int r = flat / CH, pos = flat % CH;
+            const int c = D == 128 ? (pos ^ swz16(r)) : (pos ^ ((r >> 1) & 7));
+            qrow_l[ci] = r;
+            qvoff[ci] = (uint32_t)c * 16u;
+        }
+        auto issue_item = [&](int item, int buf) {
+            const int hg = item / (n_rb - rb_first), rb = rb_first + item % (n_rb - rb_first);
+            const int h = g * p.G + hg;
+            const int i0 = iw0 + 32 * rb;
+#pragma unroll
+            for (int ci = 0; ci < NLD; ++ci) {
+                const int i = min(i0 + qrow_l[ci], nq - 1);
+                dma16_to_lds(rsQ, q_lds + buf * QBLK_BYTES + 1024 * (wave + kImpWaves * ci),
+                             (uint32_t)i * q_row_bytes + (uint32_t)h * (uint32_t)p.q_sh * 2u + qvoff[ci]);
+            }
+            if (tid < 32) {
+                const int i = min(i0 + tid, nq - 1);
+                lse_lds[buf][tid] = p.lse[(int64_t)h * p.total_q + qs + i] * kLog2e;
+            }
+        };
+        // A-operand read address of row n, chunk 2 kk + hh
+        uint32_t qaddr[NKK];
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+            const int c = 2 * kk + hh;
+            const int cs = D == 128 ? (c ^ swz16(n)) : (c ^ ((n >> 1) & 7));
+            qaddr[kk] = (uint32_t)n * ROW_BYTES + (uint32_t)cs * 16u;
+        }
+
+        if (n_items > 0) issue_item(0, 0);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        for (int item = 0; item < n_items; ++item) {
+            const int buf = item & 1;
+            if (item + 1 < n_items) issue_item(item + 1, buf ^ 1);
+            const int rb = rb_first + item % (n_rb - rb_first);
+            const int i0 = iw0 + 32 * rb;
+            const int i_last = min(i0 + 31, nq - 1);
+            if (jw0 <= i_last + delta && jw0 < nk) {       // some row of the block sees some key of the wave
+                const uint8_t *qb = &qs_lds[buf][0];
+                f32x16 s0, s1;
+                const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < NKK; ++kk) {
-                    const bf16x8 a = *(const bf16x8 *)(qp + 16 * kk);
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[kk], s, 0, 0, 0);
+                    const bf16x8 a = *(const bf16x8 *)(qb + qaddr[kk]);
+                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[0][kk], kk == 0 ? zero16 : s0, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[1][kk], kk == 0 ? zero16 : s1, 0, 0, 0);
                 }
+                // log2-domain LSE of rows 8 (e/4) + 4 hh + (e%4)
+                f32x4 l2[4];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int i = i0 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    const bool ok = (i < nq) && (j <= i + delta) && (j < nk);
-                    const float l2 = lse_h[min(i, nq - 1)] * kLog2e;
-                    const float pr = fast_exp2(fmaf(s[e], c2, -l2));
-                    colsum += ok ? pr : 0.f;
+                for (int bq = 0; bq < 4; ++bq) l2[bq] = *(const f32x4 *)&lse_lds[buf][8 * bq + 4 * hh];
+                // rows beyond the sequence end or keys beyond a row's reach contribute nothing
+                const bool partial = (i0 + 31 > nq - 1) || (jw0 + 63 > i0 + delta) || (jw0 + 63 > nk - 1);
+                if (!partial) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        colsum[0] += fast_exp2(fmaf(s0[e], c2, -l2[e >> 2][e & 3]));
+                        colsum[1] += fast_exp2(fmaf(s1[e], c2, -l2[e >> 2][e & 3]));
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int i = i0 + 8 * (e >> 2) + 4 * hh + (e & 3);
+                        const float p0 = fast_exp2(fmaf(s0[e], c2, -l2[e >> 2][e & 3]));
+                        const float p1 = fast_exp2(fmaf(s1[e], c2, -l2[e >> 2][e & 3]));
+                        colsum[0] += (i < nq && jkey[0] <= i + delta && jkey[0] < nk) ? p0 : 0.f;
+                        colsum[1] += (i < nq && jkey[1] <= i + delta && jkey[1] < nk) ? p1 : 0.f;
+                    }
                 }
             }
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
         }
     }
-    colsum += xchg_half(colsum);
-    if (hh == 0 && j < nk) p.imp[(int64_t)g * p.total_k + ks + j] = colsum;
+#pragma unroll
+    for (int kg = 0; kg < 2; ++kg) {
+        const float tot = colsum[kg] + xchg_half(colsum[kg]);
+        if (hh == 0 && jkey[kg] < nk) p.imp[(int64_t)g * p.total_k + ks + jkey[kg]] = tot;
+    }
+#else
+    (void)p;
+#endif
 }
 
 }  // namespace pdd
