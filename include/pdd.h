@@ -180,9 +180,8 @@ size_t pdd_workspace_bytes(const pdd_attn_desc *desc, int which_call);
 
 /*
  * Tuning knobs (process-wide, not thread-safe against concurrent launches).
- *   PDD_OPT_ATTN_WAVES: attention kernel variant: 4 or 8 wavefronts of 32
- *   queries per workgroup, or 64 = four wavefronts of 64 queries (head_dim 128
- *   only; falls back to 8 otherwise); 0 = chosen per problem (default).
+ *   PDD_OPT_ATTN_WAVES: wavefronts per attention workgroup, 4 (128 queries) or
+ *   8 (256 queries); 0 = chosen per problem (default).
  */
 enum { PDD_OPT_ATTN_WAVES = 0 };
 pdd_status pdd_set_option(int option, int value);

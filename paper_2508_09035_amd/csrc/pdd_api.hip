@@ -11,7 +11,6 @@
 
 #include "attn_fwd.hpp"
 #include "attn_fwd_d128.hpp"
-#include "attn_fwd_d128_w64.hpp"
 #include "importance.hpp"
 #include "select_topk.hpp"
 
@@ -135,13 +134,11 @@ pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, con
     p.scale_log2 = scale_log2(d);
 
     // 8 waves (256 queries per workgroup) halve the K/V traffic per flop; use them when there
-    // are enough such workgroups to fill the 256 CUs twice over, else 4 waves.  The
-    // 64-queries-per-wave kernel (head_dim 128) is opt-in through PDD_OPT_ATTN_WAVES = 64.
+    // are enough such workgroups for half of the 256 CUs (measured break-even), else 4 waves.
     int nw = g_attn_waves;
     const int64_t tiles256 = (int64_t)((d->max_seqlen_q + 255) / 256) * d->batch * d->n_q_heads;
-    if (nw == 0) nw = tiles256 >= 512 ? 8 : 4;
-    if (nw == 64 && d->head_dim != 128) nw = 8;
-    const int bm = nw == 64 ? pdd::kW64BM : nw * 32;
+    if (nw == 0) nw = tiles256 >= 128 ? 8 : 4;
+    const int bm = nw * 32;
     p.n_qtiles = (d->max_seqlen_q + bm - 1) / bm;
     const int64_t blocks = (int64_t)p.n_qtiles * d->batch * d->n_q_heads;
     if (blocks > 0x7fffffffLL) return fail(PDD_ERR_INVALID_ARG, "launch grid too large");
@@ -150,9 +147,6 @@ pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, con
         const int64_t span = ((int64_t)d->max_seqlen_k + 64) * 2 *
                              (d->k_stride_tok > d->v_stride_tok ? d->k_stride_tok : d->v_stride_tok);
         if (span >= (1LL << 32)) return fail(PDD_ERR_UNSUPPORTED, "a sequence's K/V span must stay below 4 GiB");
-        if (nw == 64)
-            return launch_attn_kernel(pdd::attn_fwd_d128_w64_kernel, pdd::kAttn128Smem, pdd::kW64Waves * 64, p,
-                                      blocks, st);
         return nw == 8 ? launch_attn_t<128, 8>(p, blocks, st) : launch_attn_t<128, 4>(p, blocks, st);
     }
     return nw == 8 ? launch_attn_t<64, 8>(p, blocks, st) : launch_attn_t<64, 4>(p, blocks, st);
@@ -206,8 +200,7 @@ const char *pdd_version(void) { return "pdd 0.1 gfx950"; }
 pdd_status pdd_set_option(int option, int value)
 {
     if (option == PDD_OPT_ATTN_WAVES) {
-        if (value != 0 && value != 4 && value != 8 && value != 64)
-            return fail(PDD_ERR_INVALID_ARG, "attn waves must be 0, 4, 8 or 64");
+        if (value != 0 && value != 4 && value != 8) return fail(PDD_ERR_INVALID_ARG, "attn waves must be 0, 4 or 8");
         g_attn_waves = value;
         return PDD_OK;
     }
