@@ -286,19 +286,18 @@ pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, 
     p.scores = scores;  p.cu_k = cu_seqlens_k;  p.cand_b = cand_begin;  p.cand_e = cand_end;
     p.k_per = k_per_seq;  p.cu_keep = cu_keep;  p.out_idx = out_indices;  p.out_mask = out_mask;
     p.n_heads = n_heads;  p.B = batch;  p.total_k = total_k;  p.total_keep = total_keep;
-    p.lds_cap = (max_seqlen_k + 3) & ~3;
     const dim3 grid((unsigned)batch, (unsigned)n_heads);
     hipStream_t st = (hipStream_t)stream;
-    if (max_seqlen_k <= pdd::kSelLdsCap) {
-        auto kern = pdd::select_topk_kernel<true>;
-        const int smem = ((max_seqlen_k + 3) & ~3) * 4;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, pdd::kSelLdsCap * 4);
-        if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-        hipLaunchKernelGGL(kern, grid, dim3(pdd::kSelThreads), smem, st, p);
-    } else {
-        hipLaunchKernelGGL(pdd::select_topk_kernel<false>, grid, dim3(pdd::kSelThreads), 0, st, p);
-    }
+    if (max_seqlen_k <= 4 * pdd::kSelThreads)
+        hipLaunchKernelGGL(pdd::select_topk_reg_kernel<4>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    else if (max_seqlen_k <= 8 * pdd::kSelThreads)
+        hipLaunchKernelGGL(pdd::select_topk_reg_kernel<8>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    else if (max_seqlen_k <= 16 * pdd::kSelThreads)
+        hipLaunchKernelGGL(pdd::select_topk_reg_kernel<16>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    else if (max_seqlen_k <= 32 * pdd::kSelThreads)
+        hipLaunchKernelGGL(pdd::select_topk_reg_kernel<32>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL(pdd::select_topk_kernel, grid, dim3(pdd::kSelThreads), 0, st, p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(PDD_ERR_HIP, "select launch: %s", hipGetErrorString(e));
     return PDD_OK;

@@ -3,12 +3,22 @@
 // r and the positions are filtered; the mask tensor has 1 at position i when
 // token i is selected).
 //
-// One workgroup per (sequence, head) row.  The k-th largest score is found by
-// a 4 x 8-bit most-significant-first radix select on order-preserving integer
-// images of the fp32 scores (LDS histograms); ties at the threshold are
-// resolved towards the lower index.  The kept indices are then written in
-// ascending order by a ballot / popcount compaction (each wave owns a
-// contiguous slice, so the output order is the index order).
+// One workgroup of 1024 threads per (sequence, head) row; scores become
+// order-preserving uint32 keys.  Two kernels:
+//
+//  * select_topk_reg_kernel<EPT> (rows of up to 1024*EPT <= 32768 candidates):
+//    every thread keeps its EPT keys in registers for the whole kernel.  The
+//    k-th largest key is found by bisection on the key value inside the row's
+//    [min, max] range: one step = EPT compares per lane, wave ballots counted
+//    on the scalar unit, one 16-entry LDS exchange.  No LDS atomics (measured
+//    at ~30 cycles per wave instruction, they dominated the radix variant)
+//    and no re-reading of the row.  The kept indices are written in ascending
+//    order from ballot prefix counts, with a 16*EPT-entry scan across waves.
+//  * select_topk_kernel (longer rows): most-significant-first radix select,
+//    8 bits per pass, digits taken from (key - min key) scaled to the row's
+//    range, LDS histograms; the row is re-read from L2 in every pass.
+//
+// Ties at the threshold are resolved towards the lower index in both.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -21,12 +31,11 @@ struct SelParams {
     int32_t *out_idx;
     uint8_t *out_mask;
     int32_t n_heads, B, total_k, total_keep;
-    int32_t lds_cap;   // scores staged per row (STAGED variant): longer rows are truncated
 };
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kSelLdsCap = 32768;   // scores staged in LDS up to this row length
+constexpr int kSelRegCap = 32 * 1024;  // rows up to this many candidates stay in registers
 
 __device__ __forceinline__ uint32_t order_key(float x)
 {
@@ -35,20 +44,18 @@ __device__ __forceinline__ uint32_t order_key(float x)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-template <bool STAGED>
-__device__ __forceinline__ uint32_t sel_key(const uint32_t *skeys, const float *row, int idx)
-{
-    return STAGED ? skeys[idx] : order_key(row[idx]);
-}
 
-template <bool STAGED>
-__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParams p)
+// ---------------------------------------------------------------------------
+// Register-resident selection for rows of at most 1024 * EPT candidates.
+// Thread `tid` owns candidates x = i * 1024 + tid, i = 0 .. EPT-1.
+// ---------------------------------------------------------------------------
+template <int EPT>
+__global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelParams p)
 {
-    extern __shared__ __attribute__((aligned(16))) uint32_t sel_smem[];
-    __shared__ uint32_t hist[256];
-    __shared__ int32_t sh_bin, sh_above;
-    __shared__ int32_t wave_gt[kSelWaves], wave_eq[kSelWaves];
-    uint32_t *skeys = sel_smem;
+    __shared__ uint32_t wred[2][kSelWaves];            // per-wave partial counts (double buffered)
+    __shared__ uint32_t wave_min[kSelWaves], wave_max[kSelWaves];
+    __shared__ uint32_t cnt[kSelWaves * EPT];          // per (i, wave): gt count | eq count << 16
+    __shared__ uint32_t cnt_wave_tot[kSelWaves];
 
     const int b = blockIdx.x, g = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -59,7 +66,133 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
     int c1 = p.cand_e ? p.cand_e[b] : nk;
     c0 = min(max(c0, 0), nk);
     c1 = min(max(c1, c0), nk);
-    const int n = STAGED ? min(c1 - c0, p.lds_cap) : c1 - c0;
+    const int n = min(c1 - c0, kSelThreads * EPT);
+    const int keep0 = min(max(p.cu_keep[b], 0), p.total_keep);
+    const int keep1 = min(max(p.cu_keep[b + 1], keep0), p.total_keep);
+    const int slots = keep1 - keep0;
+    const int kk = min(min(max(p.k_per[b], 0), n), slots);
+
+    const float *row = p.scores + (int64_t)g * p.total_k + ks + c0;
+    int32_t *out = p.out_idx + (int64_t)g * p.total_keep + keep0;
+    uint8_t *mrow = p.out_mask ? p.out_mask + (int64_t)g * p.total_k + ks : nullptr;
+
+    if (mrow) {
+        for (int x = tid; x < c0; x += kSelThreads) mrow[x] = 0;
+        for (int x = c0 + n + tid; x < nk; x += kSelThreads) mrow[x] = 0;
+    }
+    for (int x = kk + tid; x < slots; x += kSelThreads) out[x] = -1;
+    if (kk == 0) {
+        if (mrow)
+            for (int x = c0 + tid; x < c0 + n; x += kSelThreads) mrow[x] = 0;
+        return;
+    }
+
+    // ---- keys into registers; row range
+    uint32_t key[EPT];
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const int x = i * kSelThreads + tid;
+        const bool in = x < n;
+        key[i] = in ? order_key(row[x]) : 0u;
+        kmin = in ? min(kmin, key[i]) : kmin;
+        kmax = in ? max(kmax, key[i]) : kmax;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
+    }
+    if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
+
+    // ---- bisection: largest T in [kmin, kmax] with count(key >= T) >= kk.
+    // Invalid slots hold key 0 and every probed T is > kmin >= 0, so they never count.
+    uint32_t lo = kmin, hi = kmax;
+    uint32_t c_above = 0;              // count(key >= hi + 1) = count(key > T) at the end
+    int par = 0;
+    while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+        uint32_t c = 0;
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) c += (uint32_t)__popcll(__ballot(key[i] >= mid));
+        if (lane == 0) wred[par][wave] = c;
+        __syncthreads();
+        uint32_t tot = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) tot += wred[par][w];
+        par ^= 1;
+        if (tot >= (uint32_t)kk) lo = mid;
+        else { hi = mid - 1u; c_above = tot; }
+    }
+    const uint32_t T = lo;
+    const int krem = kk - (int)c_above;     // ties at T to keep (>= 1), lowest index first
+
+    // ---- per (i, wave) counts of keys > T and == T, scanned in index order (i major, wave minor)
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const bool in = i * kSelThreads + tid < n;
+        const uint32_t cg = (uint32_t)__popcll(__ballot(in && key[i] > T));
+        const uint32_t ce = (uint32_t)__popcll(__ballot(in && key[i] == T));
+        if (lane == i) mine = cg | (ce << 16);
+    }
+    if (lane < EPT) cnt[lane * kSelWaves + wave] = mine;
+    __syncthreads();
+    constexpr int NC = kSelWaves * EPT;                 // <= 512 entries, one per thread
+    uint32_t v = tid < NC ? cnt[tid] : 0u, incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, off, 64);
+        if (lane >= off) incl += o;
+    }
+    if (lane == 63) cnt_wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t wave_off = 0;
+    for (int w = 0; w < wave; ++w) wave_off += cnt_wave_tot[w];
+    if (tid < NC) cnt[tid] = wave_off + incl - v;       // exclusive prefix (packed gt | eq << 16)
+    __syncthreads();
+
+    // ---- stable compaction
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const int x = i * kSelThreads + tid;
+        const bool in = x < n;
+        const uint32_t before = cnt[i * kSelWaves + wave];
+        const int gt_before = (int)(before & 0xffffu), eq_before = (int)(before >> 16);
+        const bool is_gt = in && key[i] > T, is_eq = in && key[i] == T;
+        const uint64_t be = __ballot(is_eq);
+        const int eq_rank = eq_before + __popcll(be & lt_mask);
+        const bool sel = is_gt || (is_eq && eq_rank < krem);
+        const uint64_t bs = __ballot(sel);
+        const int sel_before = gt_before + min(eq_before, krem);
+        if (sel) out[sel_before + __popcll(bs & lt_mask)] = c0 + x;
+        if (mrow && in) mrow[c0 + x] = sel ? 1 : 0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Radix selection for rows longer than 32768 candidates (keys re-read from L2).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParams p)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ int32_t sh_bin, sh_above;
+    __shared__ int32_t wave_gt[kSelWaves], wave_eq[kSelWaves];
+
+    const int b = blockIdx.x, g = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ks = min(max(p.cu_k[b], 0), p.total_k);
+    const int ke = min(max(p.cu_k[b + 1], ks), p.total_k);
+    const int nk = ke - ks;
+    int c0 = p.cand_b ? p.cand_b[b] : 0;
+    int c1 = p.cand_e ? p.cand_e[b] : nk;
+    c0 = min(max(c0, 0), nk);
+    c1 = min(max(c1, c0), nk);
+    const int n = c1 - c0;
     const int keep0 = min(max(p.cu_keep[b], 0), p.total_keep);
     const int keep1 = min(max(p.cu_keep[b + 1], keep0), p.total_keep);
     const int slots = keep1 - keep0;
@@ -81,48 +214,75 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
         return;
     }
 
-    if (STAGED) {
-        for (int x = tid; x < n; x += kSelThreads) skeys[x] = order_key(row[x]);
+    // ---- the row's key range
+    __shared__ uint32_t wave_min[kSelWaves], wave_max[kSelWaves];
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll 8
+    for (int x = tid; x < n; x += kSelThreads) {
+        const uint32_t key = order_key(row[x]);
+        kmin = min(kmin, key);
+        kmax = max(kmax, key);
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
+    }
+    if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
+    const uint32_t range = kmax - kmin;
+    const int nbits = 32 - __builtin_clz(range | 1u);        // 1 .. 32
+    const int passes = (nbits + 7) >> 3;                     // 1 .. 4
+    const int lsh = 8 * passes - nbits;                      // scaled key = (key - kmin) << lsh < 2^(8 passes)
+    const bool aggregate = nbits < 12;
 
-    // ---- radix select: after the loop `prefix` is the key of the kk-th largest
-    uint32_t prefix = 0, pmask = 0;
+    // ---- radix select on the scaled keys: afterwards `prefix` is the scaled key of the kk-th largest
+    uint32_t prefix = 0;
     int krem = kk;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int shift = 8 * (passes - 1 - pass);
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
+#pragma unroll 4
         for (int x0 = 0; x0 < n; x0 += kSelThreads) {
             const int x = x0 + tid;
             const bool in = x < n;
-            const uint32_t key = in ? sel_key<STAGED>(skeys, row, x) : 0u;
-            const bool part = in && ((key & pmask) == prefix);
-            const uint32_t bin = (key >> shift) & 255u;
-            // one round of wave aggregation: lanes that share the first
-            // participating lane's bin are counted with a single atomic
-            const uint64_t pm = __ballot(part);
-            if (pm) {
-                const int leader = __ffsll((unsigned long long)pm) - 1;
-                const uint32_t lbin = __shfl(bin, leader, 64);
-                const uint64_t same = __ballot(part && bin == lbin);
-                if (lane == leader) atomicAdd(&hist[lbin], (uint32_t)__popcll(same));
-                if (part && bin != lbin) atomicAdd(&hist[bin], 1u);
+            const uint32_t sk = in ? (order_key(row[x]) - kmin) << lsh : 0u;
+            // digits above the current one must equal the prefix found so far
+            const bool part = in && (pass == 0 || (sk >> (shift + 8)) == prefix);
+            const uint32_t bin = (sk >> shift) & 255u;
+            if (!aggregate) {
+                // wide key range: the scaled digits spread over the bins, plain LDS atomics
+                if (part) atomicAdd(&hist[bin], 1u);
+            } else {
+                // narrow range (many equal keys): lanes that share the first participating
+                // lane's bin are counted with a single atomic
+                const uint64_t pm = __ballot(part);
+                if (pm) {
+                    const int leader = __ffsll((unsigned long long)pm) - 1;
+                    const uint32_t lbin = __builtin_amdgcn_readlane(bin, leader);
+                    const uint64_t same = __ballot(part && bin == lbin);
+                    if (lane == leader) atomicAdd(&hist[lbin], (uint32_t)__popcll(same));
+                    if (part && bin != lbin) atomicAdd(&hist[bin], 1u);
+                }
             }
         }
         __syncthreads();
         if (wave == 0) {
             // lane L owns bins 4L .. 4L+3 ; `above` = count in bins greater than d
             uint32_t c[4];
-            uint32_t s = 0;
+            uint32_t sum4 = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { c[i] = hist[4 * lane + i]; s += c[i]; }
-            uint32_t incl = s;   // inclusive suffix sum over lanes >= L
+            for (int i = 0; i < 4; ++i) { c[i] = hist[4 * lane + i]; sum4 += c[i]; }
+            uint32_t incl = sum4;   // inclusive suffix sum over lanes >= L
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const uint32_t o = __shfl_down(incl, off, 64);
                 if (lane + off < 64) incl += o;
             }
-            uint32_t above = incl - s;
+            uint32_t above = incl - sum4;
 #pragma unroll
             for (int i = 3; i >= 0; --i) {
                 if ((uint32_t)krem > above && (uint32_t)krem <= above + c[i]) {
@@ -133,12 +293,11 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
             }
         }
         __syncthreads();
-        prefix |= ((uint32_t)sh_bin) << shift;
-        pmask |= 255u << shift;
+        prefix = (prefix << 8) | (uint32_t)sh_bin;
         krem -= sh_above;
         __syncthreads();
     }
-    const uint32_t T = prefix;   // threshold key; `krem` (>= 1) ties at T are kept, lowest index first
+    const uint32_t T = kmin + (prefix >> lsh);   // threshold key; `krem` (>= 1) ties at T are kept, lowest index first
 
     // ---- stable compaction: each wave owns a contiguous slice of the candidates
     const int seg = ((n + kSelWaves - 1) / kSelWaves + 63) & ~63;
@@ -147,7 +306,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
     for (int x0 = s0; x0 < s1; x0 += 64) {
         const int x = x0 + lane;
         const bool in = x < s1;
-        const uint32_t key = in ? sel_key<STAGED>(skeys, row, x) : 0u;
+        const uint32_t key = in ? order_key(row[x]) : 0u;
         cgt += __popcll(__ballot(in && key > T));
         ceq += __popcll(__ballot(in && key == T));
     }
@@ -160,7 +319,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
     for (int x0 = s0; x0 < s1; x0 += 64) {
         const int x = x0 + lane;
         const bool in = x < s1;
-        const uint32_t key = in ? sel_key<STAGED>(skeys, row, x) : 0u;
+        const uint32_t key = in ? order_key(row[x]) : 0u;
         const bool is_gt = in && key > T, is_eq = in && key == T;
         const uint64_t be = __ballot(is_eq);
         const int eq_rank = eq_before + __popcll(be & lt_mask);
