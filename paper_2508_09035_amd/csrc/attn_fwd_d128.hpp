@@ -196,11 +196,12 @@ void attn_fwd_d128_kernel(const AttnParams p)
         }
     };
 
+    // short dependency chains: a 3-level tree of v_max3 instead of one serial chain
     auto row_max = [&](const f32x16 &s) {
-        float tmax = max3(s[0], s[1], s[2]);
-#pragma unroll
-        for (int e = 3; e < 15; e += 2) tmax = max3(tmax, s[e], s[e + 1]);
-        tmax = fmaxf(tmax, s[15]);
+        const float t0 = max3(s[0], s[1], s[2]), t1 = max3(s[4], s[5], s[6]);
+        const float t2 = max3(s[8], s[9], s[10]), t3 = max3(s[12], s[13], s[14]);
+        const float u0 = max3(t0, t1, s[3]), u1 = max3(t2, t3, s[7]);
+        const float tmax = max3(max3(u0, u1, s[11]), s[15], s[15]);
         return fmaxf(tmax, xchg_half(tmax));
     };
 
@@ -215,13 +216,13 @@ void attn_fwd_d128_kernel(const AttnParams p)
     };
 
     auto exp_block = [&](f32x16 &s, float mc) {
-        float psum = 0.f;
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};    // four independent partial sums
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             s[e] = fast_exp2(fmaf(s[e], c2, -mc));
-            psum += s[e];
+            ps[e & 3] += s[e];
         }
-        l_run += psum;
+        l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
     };
 
     // O^T += V^T P^T for the 32-key block at byte offset `voff` of the V buffers
