@@ -171,6 +171,46 @@ pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch,
                            void *workspace, size_t workspace_bytes, pdd_stream stream);
 
 /*
+ * Selection with 1-D pooling of the scores first (Section 3.2 "Prompt Refiner":
+ * after summing the weight along the query dimension, 1-D pooling "for
+ * clustering", then sorting).  The paper gives neither kernel size nor type;
+ * both are parameters here.  Pooled score of key j = reduction over keys
+ * [j - r, j + r] of the same sequence, r = (pool_kernel - 1) / 2, stride 1:
+ *   PDD_POOL_MAX  maximum over the part of the window inside the sequence
+ *   PDD_POOL_AVG  sum over that part divided by pool_kernel (zero padding)
+ *   PDD_POOL_NONE the raw scores (pool_kernel ignored)
+ * The pooled scores are ranked exactly like pdd_select_topk ranks raw scores
+ * (same arguments, same outputs).  pool_kernel must be odd, 1 .. 1025.
+ *   pooled_out  DEVICE fp32 [n_heads, total_k] or NULL: the pooled scores   -- out
+ */
+enum { PDD_POOL_NONE = 0, PDD_POOL_MAX = 1, PDD_POOL_AVG = 2 };
+pdd_status pdd_select_topk_pooled(const float *scores, int32_t n_heads, int32_t batch,
+                                  int32_t total_k, const int32_t *cu_seqlens_k,
+                                  const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
+                                  const int32_t *cand_begin, const int32_t *cand_end,
+                                  const int32_t *k_per_seq, const int32_t *cu_keep,
+                                  int32_t total_keep, int32_t pool_kernel, int32_t pool_mode,
+                                  float *pooled_out, int32_t *out_indices, uint8_t *out_mask,
+                                  void *workspace, size_t workspace_bytes, pdd_stream stream);
+
+/*
+ * Mask -> bit stream (Section 3.2: the mask tensor is treated as a bit stream
+ * before compression).  For every row (head) and sequence b the stream starts
+ * at a byte boundary: byte j holds tokens 8j .. 8j+7 of the sequence, first
+ * token in the most significant bit, unused tail bits zero.
+ *
+ *   mask      DEVICE uint8 [n_rows, total_k], non-zero = selected          -- in
+ *   cu_bytes  DEVICE int32[B+1] prefix sums of the per-sequence byte counts,
+ *             each at least ceil(Nk_b / 8); spare bytes are written as zero;
+ *             a sequence longer than 8 * its byte count is truncated
+ *   out_bits  DEVICE uint8 [n_rows, total_bytes]                          -- out
+ */
+pdd_status pdd_pack_mask(const uint8_t *mask, int32_t n_rows, int32_t batch, int32_t total_k,
+                         const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host,
+                         int32_t max_seqlen_k, const int32_t *cu_bytes, int32_t total_bytes,
+                         uint8_t *out_bits, pdd_stream stream);
+
+/*
  * Bytes of DEVICE scratch `which_call` needs for this descriptor.  Never grows
  * with Nq*Nk: the attention weights are not materialised (Section 3.2
  * "Preliminaries").  For PDD_CALL_SELECT_TOPK only batch, n_kv_heads,

@@ -16,8 +16,10 @@ from .core import (
     attention,
     importance,
     select_topk,
+    pack_mask,
+    pool_scores,
     num_threads,
     widen_bf16,
 )
 
-__all__ = ["build", "attention", "importance", "select_topk", "num_threads", "widen_bf16"]
+__all__ = ["build", "attention", "importance", "select_topk", "pack_mask", "pool_scores", "num_threads", "widen_bf16"]

@@ -143,3 +143,41 @@ def select_topk(scores: np.ndarray, cu_k, k_per_seq, cand_begin=None, cand_end=N
             idx_out[g, cu_keep[b]:cu_keep[b + 1]] = keep
             mask[g, cu_k[b] + keep] = 1
     return idx_out, mask
+
+
+def pack_mask(mask: np.ndarray, cu_k):
+    """Mask -> bit stream per (row, sequence), byte aligned, first token in the
+    most significant bit (Section 3.2: the mask is treated as a bit stream).
+    Returns (bits uint8 [rows, sum ceil(n_b/8)], cu_bytes)."""
+    mask = np.asarray(mask, dtype=np.uint8)
+    cu_k = np.asarray(cu_k, dtype=np.int64)
+    nbytes = [(int(cu_k[b + 1] - cu_k[b]) + 7) // 8 for b in range(len(cu_k) - 1)]
+    cu_bytes = np.concatenate([[0], np.cumsum(nbytes)]).astype(np.int32)
+    out = np.zeros((mask.shape[0], int(cu_bytes[-1])), dtype=np.uint8)
+    for r in range(mask.shape[0]):
+        for b in range(len(cu_k) - 1):
+            seg = (mask[r, cu_k[b]:cu_k[b + 1]] != 0).astype(np.uint8)
+            out[r, cu_bytes[b]:cu_bytes[b + 1]] = np.packbits(seg)   # bitorder 'big'
+    return out, cu_bytes
+
+
+def pool_scores(scores: np.ndarray, cu_k, kernel: int, mode: str) -> np.ndarray:
+    """1-D pooling of the summed scores along each sequence before sorting
+    (Section 3.2 "Prompt Refiner": "applying 1D pooling for clustering").
+    Window of key j: keys [j - r, j + r] of the same sequence, r = (kernel-1)/2.
+    mode "max": maximum over the part of the window inside the sequence;
+    mode "avg": sum over that part divided by `kernel` (zero padding).
+    The paper states neither size nor type; both are parameters."""
+    scores = np.asarray(scores, dtype=np.float64)
+    cu_k = np.asarray(cu_k, dtype=np.int64)
+    assert kernel >= 1 and kernel % 2 == 1 and mode in ("max", "avg")
+    r = (kernel - 1) // 2
+    out = np.empty_like(scores)
+    for g in range(scores.shape[0]):
+        for b in range(len(cu_k) - 1):
+            seq = scores[g, cu_k[b]:cu_k[b + 1]]
+            n = len(seq)
+            for j in range(n):
+                win = seq[max(0, j - r):min(n, j + r + 1)]
+                out[g, cu_k[b] + j] = win.max() if mode == "max" else win.sum() / kernel
+    return out

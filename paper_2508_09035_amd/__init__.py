@@ -15,6 +15,11 @@ from .binding import (
     prefill_attn_chunked,
     token_importance,
     select_topk,
+    select_topk_pooled,
+    POOL_NONE,
+    POOL_MAX,
+    POOL_AVG,
+    pack_mask,
     workspace_bytes,
     AttnDesc,
     make_desc,
@@ -23,6 +28,6 @@ from .binding import (
 
 __all__ = [
     "PddError", "library_path", "load_library", "version", "set_option", "prefill_attn",
-    "prefill_attn_chunked", "token_importance", "select_topk", "workspace_bytes", "AttnDesc",
+    "prefill_attn_chunked", "token_importance", "select_topk", "select_topk_pooled", "POOL_NONE", "POOL_MAX", "POOL_AVG", "pack_mask", "workspace_bytes", "AttnDesc",
     "make_desc", "OPT_ATTN_WAVES",
 ]

@@ -62,6 +62,11 @@ def load_library():
     lib.pdd_select_topk.restype = ctypes.c_int
     lib.pdd_select_topk.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp,
                                     vp, sz, vp]
+    lib.pdd_select_topk_pooled.restype = ctypes.c_int
+    lib.pdd_select_topk_pooled.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, vp, vp, vp, i32, i32,
+                                           i32, vp, vp, vp, vp, sz, vp]
+    lib.pdd_pack_mask.restype = ctypes.c_int
+    lib.pdd_pack_mask.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, i32, vp, vp]
     lib.pdd_workspace_bytes.restype = sz
     lib.pdd_workspace_bytes.argtypes = [dp, ctypes.c_int]
     lib.pdd_last_error.restype = ctypes.c_char_p
@@ -194,4 +199,34 @@ def select_topk(scores, cu_seqlens_k, max_seqlen_k, k_per_seq, cu_keep, total_ke
         _ptr(k_per_seq), _ptr(cu_keep), int(total_keep), _ptr(out_indices), _ptr(out_mask),
         _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
         _stream()))
+    del kh
+
+
+POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
+
+
+def select_topk_pooled(scores, cu_seqlens_k, max_seqlen_k, k_per_seq, cu_keep, total_keep,
+                       out_indices, out_mask=None, pool_kernel=1, pool_mode=POOL_NONE,
+                       pooled_out=None, cand_begin=None, cand_end=None, cu_seqlens_k_host=None):
+    """pdd_select_topk_pooled: 1-D pooling (max / zero-padded average, odd kernel) of the scores
+    along each sequence, then the same selection as select_topk."""
+    _check_tensors(scores, out_indices, out_mask, pooled_out)
+    kh, kh_addr = _host_i32(cu_seqlens_k_host)
+    _check(load_library().pdd_select_topk_pooled(
+        _ptr(scores), scores.shape[0], cu_seqlens_k.numel() - 1, scores.shape[1],
+        _ptr(cu_seqlens_k), kh_addr, int(max_seqlen_k), _ptr(cand_begin), _ptr(cand_end),
+        _ptr(k_per_seq), _ptr(cu_keep), int(total_keep), int(pool_kernel), int(pool_mode),
+        _ptr(pooled_out), _ptr(out_indices), _ptr(out_mask), None, 0, _stream()))
+    del kh
+
+
+def pack_mask(mask, cu_seqlens_k, max_seqlen_k, cu_bytes, total_bytes, out_bits,
+              cu_seqlens_k_host=None):
+    """pdd_pack_mask: uint8 mask [rows,total_k] -> bit stream [rows,total_bytes], per sequence
+    byte-aligned, first token in the most significant bit."""
+    _check_tensors(mask, out_bits)
+    kh, kh_addr = _host_i32(cu_seqlens_k_host)
+    _check(load_library().pdd_pack_mask(
+        _ptr(mask), mask.shape[0], cu_seqlens_k.numel() - 1, mask.shape[1], _ptr(cu_seqlens_k),
+        kh_addr, int(max_seqlen_k), _ptr(cu_bytes), int(total_bytes), _ptr(out_bits), _stream()))
     del kh

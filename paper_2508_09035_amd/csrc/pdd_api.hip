@@ -13,6 +13,7 @@
 #include "attn_fwd_d128.hpp"
 #include "importance.hpp"
 #include "select_topk.hpp"
+#include "pack_mask.hpp"
 
 namespace {
 
@@ -261,11 +262,13 @@ pdd_status pdd_token_importance(const pdd_attn_desc *desc, const void *q, const 
     return launch_importance(desc, q, k, lse, importance, desc->window, (hipStream_t)stream);
 }
 
-pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, int32_t total_k,
-                           const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
-                           const int32_t *cand_begin, const int32_t *cand_end, const int32_t *k_per_seq,
-                           const int32_t *cu_keep, int32_t total_keep, int32_t *out_indices, uint8_t *out_mask,
-                           void *workspace, size_t workspace_bytes, pdd_stream stream)
+pdd_status pdd_select_topk_pooled(const float *scores, int32_t n_heads, int32_t batch, int32_t total_k,
+                                  const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host,
+                                  int32_t max_seqlen_k, const int32_t *cand_begin, const int32_t *cand_end,
+                                  const int32_t *k_per_seq, const int32_t *cu_keep, int32_t total_keep,
+                                  int32_t pool_kernel, int32_t pool_mode, float *pooled_out,
+                                  int32_t *out_indices, uint8_t *out_mask, void *workspace,
+                                  size_t workspace_bytes, pdd_stream stream)
 {
     (void)workspace;
     (void)workspace_bytes;
@@ -278,6 +281,10 @@ pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, 
         return fail(PDD_ERR_INVALID_ARG, "cand_begin and cand_end must both be given or both be NULL");
     if (batch > 65535 * 32) return fail(PDD_ERR_INVALID_ARG, "batch too large");
     if (n_heads > 65535) return fail(PDD_ERR_INVALID_ARG, "n_heads too large");
+    if (pool_mode != PDD_POOL_NONE && pool_mode != PDD_POOL_MAX && pool_mode != PDD_POOL_AVG)
+        return fail(PDD_ERR_INVALID_ARG, "unknown pool_mode %d", pool_mode);
+    if (pool_mode != PDD_POOL_NONE && (pool_kernel < 1 || pool_kernel % 2 == 0 || pool_kernel > 1025))
+        return fail(PDD_ERR_INVALID_ARG, "pool_kernel must be odd and in [1, 1025]");
     pdd_status s = check_cu_host("cu_seqlens_k_host", cu_seqlens_k_host, batch, total_k, max_seqlen_k);
     if (s) return s;
     if (total_k == 0) return PDD_OK;
@@ -286,6 +293,10 @@ pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, 
     p.scores = scores;  p.cu_k = cu_seqlens_k;  p.cand_b = cand_begin;  p.cand_e = cand_end;
     p.k_per = k_per_seq;  p.cu_keep = cu_keep;  p.out_idx = out_indices;  p.out_mask = out_mask;
     p.n_heads = n_heads;  p.B = batch;  p.total_k = total_k;  p.total_keep = total_keep;
+    p.pool_r = pool_mode == PDD_POOL_NONE ? 0 : (pool_kernel - 1) / 2;
+    p.pool_mode = pool_mode == PDD_POOL_MAX ? pdd::kPoolMax : pdd::kPoolAvg;
+    p.pool_inv = pool_mode == PDD_POOL_AVG ? 1.0f / (float)pool_kernel : 1.0f;
+    p.pooled_out = pooled_out;
     const dim3 grid((unsigned)batch, (unsigned)n_heads);
     hipStream_t st = (hipStream_t)stream;
     if (max_seqlen_k <= 4 * pdd::kSelThreads)
@@ -300,6 +311,42 @@ pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, 
         hipLaunchKernelGGL(pdd::select_topk_kernel, grid, dim3(pdd::kSelThreads), 0, st, p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(PDD_ERR_HIP, "select launch: %s", hipGetErrorString(e));
+    return PDD_OK;
+}
+
+pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, int32_t total_k,
+                           const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
+                           const int32_t *cand_begin, const int32_t *cand_end, const int32_t *k_per_seq,
+                           const int32_t *cu_keep, int32_t total_keep, int32_t *out_indices, uint8_t *out_mask,
+                           void *workspace, size_t workspace_bytes, pdd_stream stream)
+{
+    return pdd_select_topk_pooled(scores, n_heads, batch, total_k, cu_seqlens_k, cu_seqlens_k_host, max_seqlen_k,
+                                  cand_begin, cand_end, k_per_seq, cu_keep, total_keep, 1, PDD_POOL_NONE, nullptr,
+                                  out_indices, out_mask, workspace, workspace_bytes, stream);
+}
+
+pdd_status pdd_pack_mask(const uint8_t *mask, int32_t n_rows, int32_t batch, int32_t total_k,
+                         const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
+                         const int32_t *cu_bytes, int32_t total_bytes, uint8_t *out_bits, pdd_stream stream)
+{
+    if (!mask || !cu_seqlens_k || !cu_bytes) return fail(PDD_ERR_INVALID_ARG, "NULL pointer");
+    if (n_rows < 1 || batch < 1) return fail(PDD_ERR_INVALID_ARG, "n_rows and batch must be >= 1");
+    if (total_k < 0 || total_bytes < 0 || max_seqlen_k < 0 || max_seqlen_k > total_k)
+        return fail(PDD_ERR_INVALID_ARG, "bad sizes");
+    if (total_bytes > 0 && !out_bits) return fail(PDD_ERR_INVALID_ARG, "out_bits is NULL");
+    if (batch > 65535 || n_rows > 65535) return fail(PDD_ERR_INVALID_ARG, "batch or n_rows too large");
+    pdd_status s = check_cu_host("cu_seqlens_k_host", cu_seqlens_k_host, batch, total_k, max_seqlen_k);
+    if (s) return s;
+    if (total_k == 0 || total_bytes == 0) return PDD_OK;
+    pdd::PackParams p;
+    p.mask = mask;  p.bits = out_bits;  p.cu_k = cu_seqlens_k;  p.cu_bytes = cu_bytes;
+    p.rows = n_rows;  p.B = batch;  p.total_k = total_k;  p.total_bytes = total_bytes;
+    const int max_bytes = (max_seqlen_k + 7) / 8;
+    const unsigned gx = (unsigned)((8 * max_bytes + pdd::kPackThreads - 1) / pdd::kPackThreads);
+    hipLaunchKernelGGL(pdd::pack_mask_kernel, dim3(gx, (unsigned)batch, (unsigned)n_rows), dim3(pdd::kPackThreads), 0,
+                       (hipStream_t)stream, p);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "pack launch: %s", hipGetErrorString(e));
     return PDD_OK;
 }
 

@@ -25,17 +25,39 @@
 
 namespace pdd {
 
+enum { kPoolNone = 0, kPoolMax = 1, kPoolAvg = 2 };
+
 struct SelParams {
     const float *scores;
     const int32_t *cu_k, *cand_b, *cand_e, *k_per, *cu_keep;
     int32_t *out_idx;
     uint8_t *out_mask;
     int32_t n_heads, B, total_k, total_keep;
+    int32_t pool_r, pool_mode;   // 1-D pooling radius (kernel = 2r+1) and kPool* mode; r = 0: none
+    float pool_inv;              // 1 / kernel for the average
+    float *pooled_out;           // optional [n_heads, total_k]: the pooled scores that were ranked
 };
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelRegCap = 32 * 1024;  // rows up to this many candidates stay in registers
+
+// Score of key j after 1-D pooling along the sequence (paper Section 3.2: "applying 1D
+// pooling for clustering" between the sum over queries and the sort).  Window = keys
+// [j-r, j+r] inside the sequence; max over the valid part, or sum of the valid part divided by
+// the kernel size (zero padding).  seq = first score of the sequence row, nk = its length.
+__device__ __forceinline__ float pooled_score(const float *seq, int nk, int j, int r, int mode, float inv)
+{
+    if (r == 0) return seq[j];
+    const int lo = max(j - r, 0), hi = min(j + r, nk - 1);
+    float acc = seq[lo];
+    if (mode == kPoolMax) {
+        for (int t = lo + 1; t <= hi; ++t) acc = fmaxf(acc, seq[t]);
+        return acc;
+    }
+    for (int t = lo + 1; t <= hi; ++t) acc += seq[t];
+    return acc * inv;
+}
 
 __device__ __forceinline__ uint32_t order_key(float x)
 {
@@ -72,10 +94,14 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
     const int slots = keep1 - keep0;
     const int kk = min(min(max(p.k_per[b], 0), n), slots);
 
-    const float *row = p.scores + (int64_t)g * p.total_k + ks + c0;
+    const float *seq = p.scores + (int64_t)g * p.total_k + ks;
     int32_t *out = p.out_idx + (int64_t)g * p.total_keep + keep0;
     uint8_t *mrow = p.out_mask ? p.out_mask + (int64_t)g * p.total_k + ks : nullptr;
 
+    if (p.pooled_out) {
+        float *po = p.pooled_out + (int64_t)g * p.total_k + ks;
+        for (int x = tid; x < nk; x += kSelThreads) po[x] = pooled_score(seq, nk, x, p.pool_r, p.pool_mode, p.pool_inv);
+    }
     if (mrow) {
         for (int x = tid; x < c0; x += kSelThreads) mrow[x] = 0;
         for (int x = c0 + n + tid; x < nk; x += kSelThreads) mrow[x] = 0;
@@ -94,7 +120,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
     for (int i = 0; i < EPT; ++i) {
         const int x = i * kSelThreads + tid;
         const bool in = x < n;
-        key[i] = in ? order_key(row[x]) : 0u;
+        key[i] = in ? order_key(pooled_score(seq, nk, c0 + x, p.pool_r, p.pool_mode, p.pool_inv)) : 0u;
         kmin = in ? min(kmin, key[i]) : kmin;
         kmax = in ? max(kmax, key[i]) : kmax;
     }
@@ -198,10 +224,17 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
     const int slots = keep1 - keep0;
     const int kk = min(min(max(p.k_per[b], 0), n), slots);
 
-    const float *row = p.scores + (int64_t)g * p.total_k + ks + c0;
+    const float *seq = p.scores + (int64_t)g * p.total_k + ks;
     int32_t *out = p.out_idx + (int64_t)g * p.total_keep + keep0;
     uint8_t *mrow = p.out_mask ? p.out_mask + (int64_t)g * p.total_k + ks : nullptr;
+    auto cand_key = [&](int x) {
+        return order_key(pooled_score(seq, nk, c0 + x, p.pool_r, p.pool_mode, p.pool_inv));
+    };
 
+    if (p.pooled_out) {
+        float *po = p.pooled_out + (int64_t)g * p.total_k + ks;
+        for (int x = tid; x < nk; x += kSelThreads) po[x] = pooled_score(seq, nk, x, p.pool_r, p.pool_mode, p.pool_inv);
+    }
     // mask outside the candidate range, unused index slots
     if (mrow) {
         for (int x = tid; x < c0; x += kSelThreads) mrow[x] = 0;
@@ -219,7 +252,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
     uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll 8
     for (int x = tid; x < n; x += kSelThreads) {
-        const uint32_t key = order_key(row[x]);
+        const uint32_t key = cand_key(x);
         kmin = min(kmin, key);
         kmax = max(kmax, key);
     }
@@ -249,7 +282,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
         for (int x0 = 0; x0 < n; x0 += kSelThreads) {
             const int x = x0 + tid;
             const bool in = x < n;
-            const uint32_t sk = in ? (order_key(row[x]) - kmin) << lsh : 0u;
+            const uint32_t sk = in ? (cand_key(x) - kmin) << lsh : 0u;
             // digits above the current one must equal the prefix found so far
             const bool part = in && (pass == 0 || (sk >> (shift + 8)) == prefix);
             const uint32_t bin = (sk >> shift) & 255u;
@@ -306,7 +339,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
     for (int x0 = s0; x0 < s1; x0 += 64) {
         const int x = x0 + lane;
         const bool in = x < s1;
-        const uint32_t key = in ? order_key(row[x]) : 0u;
+        const uint32_t key = in ? cand_key(x) : 0u;
         cgt += __popcll(__ballot(in && key > T));
         ceq += __popcll(__ballot(in && key == T));
     }
@@ -319,7 +352,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParam
     for (int x0 = s0; x0 < s1; x0 += 64) {
         const int x = x0 + lane;
         const bool in = x < s1;
-        const uint32_t key = in ? order_key(row[x]) : 0u;
+        const uint32_t key = in ? cand_key(x) : 0u;
         const bool is_gt = in && key > T, is_eq = in && key == T;
         const uint64_t be = __ballot(is_eq);
         const int eq_rank = eq_before + __popcll(be & lt_mask);

@@ -236,3 +236,60 @@ def test_c5_chunked_catch_up():
     o_err, swapped = run_and_compare(wl, rows=rows)
     print(f"c5: {len(rows)} rows, O err {o_err:.4f}, swapped {swapped}")
     assert swapped == 0
+
+
+# ------------------------------------------------------------------- bit stream
+def test_pack_mask_bit_exact():
+    rng = np.random.default_rng(8)
+    lens = [13, 64, 0, 1000, 7, 4096 + 3]
+    rows = 3
+    m = (rng.random((rows, sum(lens))) < 0.3).astype(np.uint8) * rng.integers(1, 255, size=(rows, sum(lens))).astype(np.uint8)
+    want, cu_bytes = oracle.pack_mask(m, np.concatenate([[0], np.cumsum(lens)]))
+    cu_k = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device="cuda")
+    out = torch.full((rows, int(cu_bytes[-1])), 0xAA, dtype=torch.uint8, device="cuda")
+    pdd.pack_mask(torch.from_numpy(m).cuda(), cu_k, max(lens), torch.from_numpy(cu_bytes).cuda(),
+                  int(cu_bytes[-1]), out, np.concatenate([[0], np.cumsum(lens)]))
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+    # end to end: the mask produced by the selection kernel
+    wl = W.make_custom("t", [300, 77], None, 4, 2, 128, 40, "3/10", seed=5)
+    dev = DeviceWorkload(wl)
+    dev.step()
+    want, cu_bytes = oracle.pack_mask(dev.mask.cpu().numpy(), wl.cu_seqlens_k)
+    out = torch.empty((wl.n_kv_heads, int(cu_bytes[-1])), dtype=torch.uint8, device="cuda")
+    pdd.pack_mask(dev.mask, dev.cu_k, dev.max_k, torch.from_numpy(cu_bytes).cuda(), int(cu_bytes[-1]), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+    assert int(np.unpackbits(out.cpu().numpy()[0]).sum()) == int(wl.k_keep.sum())
+
+
+# ------------------------------------------------------------------ 1-D pooling
+@pytest.mark.parametrize("mode,kernel", [("max", 5), ("avg", 7), ("avg", 1), ("max", 33)])
+def test_pooled_selection(mode, kernel):
+    rng = np.random.default_rng(11)
+    lens = [700, 3, 1, 5000, 40000]                 # the last row takes the long-row kernel
+    heads = 2
+    s32 = (rng.random((heads, sum(lens))) ** 6).astype(np.float32)
+    s32[1, 100:140] = 0.5                           # a plateau: ties after max pooling
+    wl = W.make_custom("t", lens, None, 1, 1, 64, 0, seed=0)
+    wl.n_kv_heads = heads
+    wl.k_keep = np.array([70, 2, 1, 1500, 4000], dtype=np.int32)
+    wl.cand_begin = np.array([10, 0, 0, 0, 100], dtype=np.int32)
+    wl.cand_end = np.array([690, 3, 1, 5000, 39000], dtype=np.int32)
+    want_pooled = oracle.pool_scores(s32.astype(np.float64), wl.cu_seqlens_k, kernel, mode)
+    dev = DeviceWorkload(wl)
+    dev.poison()
+    pooled = torch.full((heads, sum(lens)), float("nan"), dtype=torch.float32, device="cuda")
+    pdd.select_topk_pooled(torch.from_numpy(s32).cuda(), dev.cu_k, dev.max_k, dev.k_keep, dev.cu_keep,
+                           dev.total_keep, dev.idx, dev.mask, kernel,
+                           pdd.POOL_MAX if mode == "max" else pdd.POOL_AVG, pooled,
+                           dev.cand_b, dev.cand_e, wl.cu_seqlens_k)
+    torch.cuda.synchronize()
+    got_pooled = pooled.cpu().numpy().astype(np.float64)
+    if mode == "max":
+        assert np.array_equal(got_pooled, want_pooled)            # exact: a maximum of fp32 values
+    else:
+        np.testing.assert_allclose(got_pooled, want_pooled, rtol=1e-6, atol=1e-12)
+    # the selection is exact on the scores the kernel ranked, and matches the fp64 pooling up to ties
+    check_selection(got_pooled, dev.idx.cpu().numpy(), dev.mask.cpu().numpy(), wl, -1, "pooled fp32")
+    check_selection(want_pooled, dev.idx.cpu().numpy(), dev.mask.cpu().numpy(), wl, 1e-6, "pooled fp64")

@@ -312,3 +312,43 @@ def test_workload_recipes():
     assert c5.cand_end.tolist() == [64] * 4 and c5.seqlens_k.tolist() == [320] * 4
     x = np.array([1.0, 1.00390625, 1.01171875, -3.5e-41], dtype=np.float32)
     assert W.f32_to_bf16_bits(x).tolist()[:3] == [0x3F80, 0x3F80, 0x3F82]
+
+
+# ---------------------------------------------------------------- bit stream
+def test_pack_mask_hand_example_and_roundtrip():
+    """Tokens [1,0,0,0,0,0,0,1 | 1,1] then [0,1,0]: first token in the most
+    significant bit, each sequence byte aligned -> 0b10000001, 0b11000000, 0b01000000."""
+    bits, cu_bytes = oracle.pack_mask(np.array([[1, 0, 0, 0, 0, 0, 0, 1, 1, 1, 0, 1, 0]]), [0, 10, 13])
+    assert bits.tolist() == [[0x81, 0xC0, 0x40]] and cu_bytes.tolist() == [0, 2, 3]
+    rng = np.random.default_rng(4)
+    lens = [5, 16, 0, 37]
+    m = rng.integers(0, 2, size=(3, sum(lens))).astype(np.uint8)
+    bits, cb = oracle.pack_mask(m * 7, cu(lens))          # any non-zero byte counts as selected
+    cuk = cu(lens)
+    for r in range(3):
+        for b, n in enumerate(lens):
+            got = [(bits[r, cb[b] + j // 8] >> (7 - j % 8)) & 1 for j in range(n)]
+            assert got == m[r, cuk[b]:cuk[b + 1]].tolist()
+            tail = bits[r, cb[b]:cb[b + 1]]
+            if n % 8:
+                assert tail[-1] & ((1 << (8 - n % 8)) - 1) == 0     # unused tail bits are zero
+
+
+# ---------------------------------------------------------------- 1-D pooling
+def test_pool_scores_hand_example_and_library_special_case():
+    s = np.array([[1.0, 5.0, 2.0, 0.0, 4.0, 3.0, 9.0]])
+    got = oracle.pool_scores(s, [0, 4, 7], 3, "max")        # two sequences: [1,5,2,0] and [4,3,9]
+    assert got.tolist() == [[5.0, 5.0, 5.0, 2.0, 4.0, 9.0, 9.0]]
+    got = oracle.pool_scores(s, [0, 4, 7], 3, "avg")        # zero padding, divide by 3
+    np.testing.assert_allclose(got, [[2.0, 8 / 3, 7 / 3, 2 / 3, 7 / 3, 16 / 3, 4.0]], rtol=1e-15)
+    assert np.array_equal(oracle.pool_scores(s, [0, 4, 7], 1, "avg"), s)
+    # one sequence: equals the library's pooling with padding k//2, stride 1
+    import torch
+    import torch.nn.functional as F
+    x = np.random.default_rng(0).random((3, 50))
+    for k in (3, 5, 9):
+        t = torch.from_numpy(x)[None]
+        np.testing.assert_allclose(oracle.pool_scores(x, [0, 50], k, "max"),
+                                   F.max_pool1d(t, k, stride=1, padding=k // 2)[0].numpy(), rtol=0)
+        np.testing.assert_allclose(oracle.pool_scores(x, [0, 50], k, "avg"),
+                                   F.avg_pool1d(t, k, stride=1, padding=k // 2)[0].numpy(), rtol=1e-14)
