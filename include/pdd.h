@@ -194,6 +194,42 @@ pdd_status pdd_select_topk_pooled(const float *scores, int32_t n_heads, int32_t 
                                   void *workspace, size_t workspace_bytes, pdd_stream stream);
 
 /*
+ * Sentence-level selection (Section 3.2 "Prompt Refiner": the KV cache entries
+ * of one sentence are combined and treated as a whole, so selecting KV cache
+ * entries means selecting sentences; prefix and suffix of the prompt are not
+ * refined).  Sentences are contiguous token ranges tiling the content part of
+ * sequence b: sentence s (cu_sent[b] <= s < cu_sent[b+1]) covers tokens
+ * [start_s, sent_end[s]) with start_s = cand_begin[b] for the first sentence and
+ * sent_end[s-1] otherwise (sequence-local offsets, non-decreasing; out-of-range
+ * values are clamped).  The paper does not say how token scores are combined:
+ * agg_mode PDD_SENT_SUM adds them, PDD_SENT_MEAN divides the sum by the length.
+ * Sentences are ranked by (score descending, index ascending) and the longest
+ * prefix of the ranking whose total token count is <= token_budget[b] is kept,
+ * so the refined length never exceeds the budget (k = floor(r * l), Eq. 5).
+ *
+ *   scores          DEVICE fp32 [n_heads, total_k]                          -- in
+ *   cu_sent         DEVICE int32[B+1], sent_end DEVICE int32[total_sent]    -- in
+ *   max_sent_per_seq host bound on sentences per sequence (<= 8192)
+ *   cand_begin      DEVICE int32[B] or NULL (= 0)
+ *   token_budget    DEVICE int32[B]
+ *   out_sent_scores DEVICE fp32 [n_heads, total_sent] or NULL               -- out
+ *   out_sent_keep   DEVICE uint8 [n_heads, total_sent] or NULL, 1 = kept    -- out
+ *   out_mask        DEVICE uint8 [n_heads, total_k] or NULL: 1 for the tokens
+ *                   of kept sentences, 0 elsewhere (also outside the content) -- out
+ *   out_kept_tokens DEVICE int32 [n_heads, B] or NULL                       -- out
+ */
+enum { PDD_SENT_SUM = 0, PDD_SENT_MEAN = 1 };
+pdd_status pdd_select_sentences(const float *scores, int32_t n_heads, int32_t batch,
+                                int32_t total_k, const int32_t *cu_seqlens_k,
+                                const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
+                                const int32_t *cu_sent, const int32_t *sent_end,
+                                int32_t total_sent, int32_t max_sent_per_seq,
+                                const int32_t *cand_begin, const int32_t *token_budget,
+                                int32_t agg_mode, float *out_sent_scores,
+                                uint8_t *out_sent_keep, uint8_t *out_mask,
+                                int32_t *out_kept_tokens, pdd_stream stream);
+
+/*
  * Mask -> bit stream (Section 3.2: the mask tensor is treated as a bit stream
  * before compression).  For every row (head) and sequence b the stream starts
  * at a byte boundary: byte j holds tokens 8j .. 8j+7 of the sequence, first

@@ -18,8 +18,9 @@ from .core import (
     select_topk,
     pack_mask,
     pool_scores,
+    select_sentences,
     num_threads,
     widen_bf16,
 )
 
-__all__ = ["build", "attention", "importance", "select_topk", "pack_mask", "pool_scores", "num_threads", "widen_bf16"]
+__all__ = ["build", "attention", "importance", "select_topk", "pack_mask", "pool_scores", "select_sentences", "num_threads", "widen_bf16"]

@@ -181,3 +181,53 @@ def pool_scores(scores: np.ndarray, cu_k, kernel: int, mode: str) -> np.ndarray:
                 win = seq[max(0, j - r):min(n, j + r + 1)]
                 out[g, cu_k[b] + j] = win.max() if mode == "max" else win.sum() / kernel
     return out
+
+
+def select_sentences(scores, cu_k, cu_sent, sent_end, token_budget, mode="mean", cand_begin=None,
+                     sum_dtype=np.float64):
+    """Sentence-level selection (Section 3.2 "Prompt Refiner": the KV cache of one
+    sentence is treated as a whole, so selection means selecting sentences).
+    Sentence s of sequence b covers tokens [start, sent_end[s]), start = cand_begin[b]
+    for the first sentence, else the previous end.  Score = sum (or mean) of the
+    token scores, added in token order in `sum_dtype`; sentences ranked by (score
+    descending, index ascending); the longest ranking prefix whose token count is
+    <= token_budget[b] is kept.
+    Returns (sent_scores [H,total_sent], sent_keep uint8 [H,total_sent],
+    mask uint8 [H,total_k], kept_tokens int32 [H,B])."""
+    scores = np.asarray(scores)
+    cu_k = np.asarray(cu_k, dtype=np.int64)
+    cu_sent = np.asarray(cu_sent, dtype=np.int64)
+    sent_end = np.asarray(sent_end, dtype=np.int64)
+    H, B = scores.shape[0], len(cu_k) - 1
+    sscore = np.zeros((H, len(sent_end)), dtype=np.float64)
+    skeep = np.zeros((H, len(sent_end)), dtype=np.uint8)
+    mask = np.zeros((H, int(cu_k[-1])), dtype=np.uint8)
+    kept = np.zeros((H, B), dtype=np.int32)
+    for g in range(H):
+        for b in range(B):
+            n = int(cu_k[b + 1] - cu_k[b])
+            c0 = 0 if cand_begin is None else int(cand_begin[b])
+            ends = sent_end[cu_sent[b]:cu_sent[b + 1]]
+            starts = np.concatenate([[c0], ends[:-1]]) if len(ends) else ends
+            assert all(0 <= s <= e <= n for s, e in zip(starts, ends))
+            vals = []
+            for s, e in zip(starts, ends):
+                acc = sum_dtype(0)
+                for x in range(int(s), int(e)):
+                    acc = sum_dtype(acc + sum_dtype(scores[g, cu_k[b] + x]))
+                if mode == "mean":
+                    acc = sum_dtype(acc / sum_dtype(max(int(e - s), 1)))
+                vals.append(float(acc))
+            vals = np.array(vals, dtype=np.float64)
+            sscore[g, cu_sent[b]:cu_sent[b + 1]] = vals
+            order = np.lexsort((np.arange(len(vals)), -vals))
+            total = 0
+            for s in order:
+                ln = int(ends[s] - starts[s])
+                if total + ln > int(token_budget[b]):
+                    break
+                total += ln
+                skeep[g, cu_sent[b] + s] = 1
+                mask[g, cu_k[b] + starts[s]: cu_k[b] + ends[s]] = 1
+            kept[g, b] = total
+    return sscore, skeep, mask, kept

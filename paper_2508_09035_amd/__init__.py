@@ -19,6 +19,9 @@ from .binding import (
     POOL_NONE,
     POOL_MAX,
     POOL_AVG,
+    select_sentences,
+    SENT_SUM,
+    SENT_MEAN,
     pack_mask,
     workspace_bytes,
     AttnDesc,
@@ -28,6 +31,6 @@ from .binding import (
 
 __all__ = [
     "PddError", "library_path", "load_library", "version", "set_option", "prefill_attn",
-    "prefill_attn_chunked", "token_importance", "select_topk", "select_topk_pooled", "POOL_NONE", "POOL_MAX", "POOL_AVG", "pack_mask", "workspace_bytes", "AttnDesc",
+    "prefill_attn_chunked", "token_importance", "select_topk", "select_topk_pooled", "POOL_NONE", "POOL_MAX", "POOL_AVG", "select_sentences", "SENT_SUM", "SENT_MEAN", "pack_mask", "workspace_bytes", "AttnDesc",
     "make_desc", "OPT_ATTN_WAVES",
 ]

@@ -65,6 +65,9 @@ def load_library():
     lib.pdd_select_topk_pooled.restype = ctypes.c_int
     lib.pdd_select_topk_pooled.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, vp, vp, vp, i32, i32,
                                            i32, vp, vp, vp, vp, sz, vp]
+    lib.pdd_select_sentences.restype = ctypes.c_int
+    lib.pdd_select_sentences.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, vp, i32, i32, vp, vp,
+                                         i32, vp, vp, vp, vp, vp]
     lib.pdd_pack_mask.restype = ctypes.c_int
     lib.pdd_pack_mask.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, i32, vp, vp]
     lib.pdd_workspace_bytes.restype = sz
@@ -217,6 +220,26 @@ def select_topk_pooled(scores, cu_seqlens_k, max_seqlen_k, k_per_seq, cu_keep, t
         _ptr(cu_seqlens_k), kh_addr, int(max_seqlen_k), _ptr(cand_begin), _ptr(cand_end),
         _ptr(k_per_seq), _ptr(cu_keep), int(total_keep), int(pool_kernel), int(pool_mode),
         _ptr(pooled_out), _ptr(out_indices), _ptr(out_mask), None, 0, _stream()))
+    del kh
+
+
+SENT_SUM, SENT_MEAN = 0, 1
+
+
+def select_sentences(scores, cu_seqlens_k, max_seqlen_k, cu_sent, sent_end, max_sent_per_seq,
+                     token_budget, agg_mode=SENT_MEAN, cand_begin=None, out_sent_scores=None,
+                     out_sent_keep=None, out_mask=None, out_kept_tokens=None,
+                     cu_seqlens_k_host=None):
+    """pdd_select_sentences: rank sentences by summed / mean token score, keep the longest
+    prefix of the ranking that fits the token budget."""
+    _check_tensors(scores, out_sent_scores, out_sent_keep, out_mask)
+    kh, kh_addr = _host_i32(cu_seqlens_k_host)
+    _check(load_library().pdd_select_sentences(
+        _ptr(scores), scores.shape[0], cu_seqlens_k.numel() - 1, scores.shape[1],
+        _ptr(cu_seqlens_k), kh_addr, int(max_seqlen_k), _ptr(cu_sent), _ptr(sent_end),
+        sent_end.numel(), int(max_sent_per_seq), _ptr(cand_begin), _ptr(token_budget),
+        int(agg_mode), _ptr(out_sent_scores), _ptr(out_sent_keep), _ptr(out_mask),
+        _ptr(out_kept_tokens), _stream()))
     del kh
 
 

@@ -14,6 +14,7 @@
 #include "importance.hpp"
 #include "select_topk.hpp"
 #include "pack_mask.hpp"
+#include "select_sentences.hpp"
 
 namespace {
 
@@ -323,6 +324,44 @@ pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch, 
     return pdd_select_topk_pooled(scores, n_heads, batch, total_k, cu_seqlens_k, cu_seqlens_k_host, max_seqlen_k,
                                   cand_begin, cand_end, k_per_seq, cu_keep, total_keep, 1, PDD_POOL_NONE, nullptr,
                                   out_indices, out_mask, workspace, workspace_bytes, stream);
+}
+
+pdd_status pdd_select_sentences(const float *scores, int32_t n_heads, int32_t batch, int32_t total_k,
+                                const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
+                                const int32_t *cu_sent, const int32_t *sent_end, int32_t total_sent,
+                                int32_t max_sent_per_seq, const int32_t *cand_begin, const int32_t *token_budget,
+                                int32_t agg_mode, float *out_sent_scores, uint8_t *out_sent_keep,
+                                uint8_t *out_mask, int32_t *out_kept_tokens, pdd_stream stream)
+{
+    if (!scores || !cu_seqlens_k || !cu_sent || !token_budget) return fail(PDD_ERR_INVALID_ARG, "NULL pointer");
+    if (total_sent > 0 && !sent_end) return fail(PDD_ERR_INVALID_ARG, "sent_end is NULL");
+    if (n_heads < 1 || batch < 1) return fail(PDD_ERR_INVALID_ARG, "n_heads and batch must be >= 1");
+    if (total_k < 0 || total_sent < 0 || max_seqlen_k < 0 || max_seqlen_k > total_k || max_sent_per_seq < 0 ||
+        max_sent_per_seq > total_sent)
+        return fail(PDD_ERR_INVALID_ARG, "bad sizes");
+    if (max_sent_per_seq > pdd::kSentMax)
+        return fail(PDD_ERR_UNSUPPORTED, "more than %d sentences in one sequence", pdd::kSentMax);
+    if (agg_mode != PDD_SENT_SUM && agg_mode != PDD_SENT_MEAN) return fail(PDD_ERR_INVALID_ARG, "unknown agg_mode");
+    if (batch > 65535 * 32 || n_heads > 65535) return fail(PDD_ERR_INVALID_ARG, "batch or n_heads too large");
+    pdd_status s = check_cu_host("cu_seqlens_k_host", cu_seqlens_k_host, batch, total_k, max_seqlen_k);
+    if (s) return s;
+    if (total_k == 0) return PDD_OK;
+    pdd::SentParams p;
+    p.scores = scores;  p.cu_k = cu_seqlens_k;  p.cu_sent = cu_sent;  p.sent_end = sent_end;
+    p.cand_b = cand_begin;  p.budget = token_budget;  p.sent_keep = out_sent_keep;  p.mask = out_mask;
+    p.kept_tokens = out_kept_tokens;  p.sent_scores = out_sent_scores;
+    p.n_heads = n_heads;  p.B = batch;  p.total_k = total_k;  p.total_sent = total_sent;
+    p.s_cap = max_sent_per_seq > 0 ? ((max_sent_per_seq + 3) & ~3) : 4;
+    p.mode = agg_mode == PDD_SENT_MEAN ? pdd::kSentMean : pdd::kSentSum;
+    const int smem = p.s_cap * 16;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pdd::select_sentences_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, pdd::kSentMax * 16);
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    hipLaunchKernelGGL(pdd::select_sentences_kernel, dim3((unsigned)batch, (unsigned)n_heads),
+                       dim3(pdd::kSelThreads), smem, (hipStream_t)stream, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "sentence select launch: %s", hipGetErrorString(e));
+    return PDD_OK;
 }
 
 pdd_status pdd_pack_mask(const uint8_t *mask, int32_t n_rows, int32_t batch, int32_t total_k,

@@ -293,3 +293,93 @@ def test_pooled_selection(mode, kernel):
     # the selection is exact on the scores the kernel ranked, and matches the fp64 pooling up to ties
     check_selection(got_pooled, dev.idx.cpu().numpy(), dev.mask.cpu().numpy(), wl, -1, "pooled fp32")
     check_selection(want_pooled, dev.idx.cpu().numpy(), dev.mask.cpu().numpy(), wl, 1e-6, "pooled fp64")
+
+
+# ------------------------------------------------- sentence-level selection
+def _sentence_split(rng, lo, hi, mean_len, with_empty):
+    """Ends of sentences tiling [lo, hi): geometric lengths, optionally a few empty ones."""
+    ends, x = [], lo
+    while x < hi:
+        x = min(hi, x + int(rng.geometric(1.0 / mean_len)))
+        ends.append(x)
+        if with_empty and rng.random() < 0.05:
+            ends.append(x)
+    return ends
+
+
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+@pytest.mark.parametrize("exact_scores", [True, False])
+def test_select_sentences(mode, exact_scores):
+    rng = np.random.default_rng(31)
+    lens = [900, 1, 0, 37, 32768, 9000]
+    heads = 2
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cb = np.array([16, 0, 0, 5, 128, 0], dtype=np.int32)
+    ce = [880, 1, 0, 30, 32768 - 64, 9000]
+    mean_len = [18, 1, 1, 4, 24, 1.2]                   # the last sequence has ~7500 sentences
+    ends, cu_sent = [], [0]
+    for b in range(len(lens)):
+        e = _sentence_split(rng, int(cb[b]), ce[b], mean_len[b], b != 5) if ce[b] > cb[b] else []
+        ends += e
+        cu_sent.append(len(ends))
+    ends = np.array(ends, dtype=np.int32)
+    cu_sent = np.array(cu_sent, dtype=np.int32)
+    max_sent = int(np.diff(cu_sent).max())
+    assert 4096 < max_sent <= 8192
+    budget = np.array([300, 1, 0, 10, 3276, 4000], dtype=np.int32)
+    if exact_scores:      # multiples of 1/64 with short sums: fp32 sums and means of sums are order-free
+        s32 = (rng.integers(0, 64, size=(heads, int(cu[-1]))) / 64.0).astype(np.float32)
+        if mode == "mean":                              # a mean is one rounded division on both sides
+            pass
+    else:
+        s32 = (rng.random((heads, int(cu[-1]))) ** 6).astype(np.float32)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    n_sent = len(ends)
+    sscore = torch.full((heads, n_sent), float("nan"), dtype=torch.float32, device="cuda")
+    skeep = torch.full((heads, n_sent), 7, dtype=torch.uint8, device="cuda")
+    mask = torch.full((heads, int(cu[-1])), 7, dtype=torch.uint8, device="cuda")
+    kept = torch.full((heads, len(lens)), -1, dtype=torch.int32, device="cuda")
+    pdd.select_sentences(d(s32), d(cu), max(lens), d(cu_sent), d(ends), max_sent, d(budget),
+                         pdd.SENT_SUM if mode == "sum" else pdd.SENT_MEAN, d(cb), sscore, skeep, mask, kept, cu)
+    torch.cuda.synchronize()
+    got_sc = sscore.cpu().numpy().astype(np.float64)
+    want_sc, want_keep, want_mask, want_kept = oracle.select_sentences(
+        s32.astype(np.float64), cu, cu_sent, ends, budget, mode, cb)
+    np.testing.assert_allclose(got_sc, want_sc, rtol=2e-6, atol=1e-12)
+    if exact_scores and mode == "sum":
+        assert np.array_equal(got_sc, want_sc)
+        assert np.array_equal(skeep.cpu().numpy(), want_keep)
+    # the decision is exact on the sentence scores the kernel ranked (fp32, as the kernel holds them):
+    # the ranking rule of the oracle applied to those scores, one token-score row per sentence
+    ln = np.concatenate([np.diff(np.concatenate([[cb[b]], ends[cu_sent[b]:cu_sent[b + 1]]]))
+                         for b in range(len(lens))]).astype(np.int64)
+    for g in range(heads):
+        for b in range(len(lens)):
+            sl = slice(cu_sent[b], cu_sent[b + 1])
+            sc_b, ln_b = got_sc[g, sl], ln[sl]
+            order = np.lexsort((np.arange(len(sc_b)), -sc_b))
+            fit = np.cumsum(ln_b[order]) <= budget[b]
+            m = int(fit.sum()) if fit.all() else int(np.argmin(fit))
+            want = np.zeros(len(sc_b), dtype=np.uint8)
+            want[order[:m]] = 1
+            assert np.array_equal(skeep.cpu().numpy()[g, sl], want), (g, b)
+            assert int(kept.cpu().numpy()[g, b]) == int(ln_b[want == 1].sum()) <= budget[b]
+    # token mask = expansion of the keep flags
+    want_m = np.zeros_like(want_mask)
+    kf = skeep.cpu().numpy()
+    for g in range(heads):
+        for b in range(len(lens)):
+            st = int(cb[b])
+            for s in range(cu_sent[b], cu_sent[b + 1]):
+                want_m[g, cu[b] + st: cu[b] + ends[s]] = kf[g, s]
+                st = int(ends[s])
+    assert np.array_equal(mask.cpu().numpy(), want_m)
+    # against the fp64 oracle: identical up to sentences whose scores tie within fp32 rounding
+    diff = kf != want_keep
+    if diff.any():
+        assert not exact_scores or mode == "mean"
+        for g, s in zip(*np.nonzero(diff)):
+            b = int(np.searchsorted(cu_sent, s, side="right") - 1)
+            sl = slice(cu_sent[b], cu_sent[b + 1])
+            others = np.delete(want_sc[g, sl], s - cu_sent[b])
+            assert np.min(np.abs(others - want_sc[g, s])) <= 4e-6 * max(abs(want_sc[g, s]), 1e-30), (g, s)

@@ -352,3 +352,71 @@ def test_pool_scores_hand_example_and_library_special_case():
                                    F.max_pool1d(t, k, stride=1, padding=k // 2)[0].numpy(), rtol=0)
         np.testing.assert_allclose(oracle.pool_scores(x, [0, 50], k, "avg"),
                                    F.avg_pool1d(t, k, stride=1, padding=k // 2)[0].numpy(), rtol=1e-14)
+
+
+# ------------------------------------------------- sentence-level selection
+def test_select_sentences_hand_example():
+    # one sequence of 12 tokens, content [2, 11): sentences [2,5) [5,6) [6,10) [10,11)
+    s = np.array([[9, 9, 1, 2, 3, 8, 1, 1, 1, 1, 5, 9]], dtype=np.float64)
+    ends = [5, 6, 10, 11]
+    # sums 6, 8, 4, 5 -> ranking 1, 0, 3, 2 with lengths 1, 3, 1, 4
+    sc, keep, mask, kept = oracle.select_sentences(s, [0, 12], [0, 4], ends, [5], "sum", [2])
+    assert sc.tolist() == [[6, 8, 4, 5]]
+    assert keep.tolist() == [[1, 1, 0, 1]] and kept.tolist() == [[5]]
+    assert mask.tolist() == [[0, 0, 1, 1, 1, 1, 0, 0, 0, 0, 1, 0]]
+    # budget 4: after sentences 1 and 0 the next one in the ranking (3, length 1) would make 5 > 4:
+    # the kept set is a PREFIX of the ranking, nothing further down is tried
+    _, keep, _, kept = oracle.select_sentences(s, [0, 12], [0, 4], ends, [4], "sum", [2])
+    assert keep.tolist() == [[1, 1, 0, 0]] and kept.tolist() == [[4]]
+    # budget 3: sentence 1 (len 1) fits, sentence 0 (len 3) does not -> stop
+    _, keep, _, kept = oracle.select_sentences(s, [0, 12], [0, 4], ends, [3], "sum", [2])
+    assert keep.tolist() == [[0, 1, 0, 0]] and kept.tolist() == [[1]]
+    # means 2, 8, 1, 5 -> ranking 1, 3, 0, 2; budget 5 keeps all but the longest
+    sc, keep, mask, kept = oracle.select_sentences(s, [0, 12], [0, 4], ends, [5], "mean", [2])
+    assert sc.tolist() == [[2, 8, 1, 5]]
+    assert keep.tolist() == [[1, 1, 0, 1]] and kept.tolist() == [[5]]
+    # budget 2 under means: ranking 1 (len 1), 3 (len 1), then 0 (len 3) stops
+    _, keep, mask, kept = oracle.select_sentences(s, [0, 12], [0, 4], ends, [2], "mean", [2])
+    assert keep.tolist() == [[0, 1, 0, 1]] and kept.tolist() == [[2]]
+    assert mask.tolist() == [[0, 0, 0, 0, 0, 1, 0, 0, 0, 0, 1, 0]]
+    # ties go to the earlier sentence
+    t = np.array([[1, 1, 1, 1]], dtype=np.float64)
+    _, keep, _, _ = oracle.select_sentences(t, [0, 4], [0, 4], [1, 2, 3, 4], [2], "sum")
+    assert keep.tolist() == [[1, 1, 0, 0]]
+
+
+def test_select_sentences_reduces_to_token_topk_and_invariants():
+    rng = np.random.default_rng(21)
+    lens = [57, 1, 200]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    s = rng.random((3, sum(lens)))
+    s[1, 60:90] = 0.25                                   # ties
+    cb = np.array([3, 0, 10]); ce = np.array([50, 1, 190]); kk = np.array([11, 1, 60])
+    # every token its own sentence: the rule becomes plain top-k over the candidate range
+    ends = np.concatenate([np.arange(cb[b] + 1, ce[b] + 1) for b in range(3)])
+    cu_sent = np.concatenate([[0], np.cumsum(ce - cb)])
+    for mode in ("sum", "mean"):
+        _, keep, mask, kept = oracle.select_sentences(s, cu, cu_sent, ends, kk, mode, cb)
+        idx, mask_tok = oracle.select_topk(s, cu, kk, cb, ce)
+        assert np.array_equal(mask, mask_tok)
+        assert np.array_equal(kept, np.tile(kk, (3, 1)))
+    # random sentence splits: the kept set is the longest ranking prefix that fits
+    for seed in range(5):
+        r = np.random.default_rng(seed)
+        n = 250
+        cuts = np.sort(r.choice(np.arange(11, 240), size=25, replace=False))
+        ends = np.concatenate([cuts, [240]])
+        sc, keep, mask, kept = oracle.select_sentences(s[:1, :n], [0, n], [0, 26], ends, [120], "mean", [10])
+        starts = np.concatenate([[10], ends[:-1]])
+        ln = ends - starts
+        np.testing.assert_allclose(sc[0], [s[0, a:b].mean() for a, b in zip(starts, ends)], rtol=1e-13)
+        assert kept[0, 0] == ln[keep[0] == 1].sum() == mask.sum() <= 120
+        assert mask[0, :10].sum() == 0 and mask[0, 240:].sum() == 0
+        for a, b, f in zip(starts, ends, keep[0]):
+            assert (mask[0, a:b] == f).all()
+        # every kept sentence outranks every dropped one, and the best dropped one does not fit
+        if (keep[0] == 0).any() and (keep[0] == 1).any():
+            assert sc[0][keep[0] == 1].min() >= sc[0][keep[0] == 0].max()
+        if (keep[0] == 0).any():
+            best_dropped = np.flatnonzero(keep[0] == 0)[np.argmax(sc[0][keep[0] == 0])]
+            assert kept[0, 0] + ln[best_dropped] > 120
