@@ -40,7 +40,8 @@ typedef enum pdd_status {
     PDD_ERR_INVALID_ARG = -1, /* null pointer, bad size, Hq % Hkv != 0, misaligned, ... */
     PDD_ERR_UNSUPPORTED = -2, /* head_dim not in {64, 128}                             */
     PDD_ERR_WORKSPACE = -3,   /* workspace smaller than pdd_workspace_bytes()           */
-    PDD_ERR_HIP = -4          /* a HIP runtime call (launch) reported an error          */
+    PDD_ERR_HIP = -4,         /* a HIP runtime call (launch) reported an error          */
+    PDD_ERR_INFEASIBLE = -5   /* pdd_choose_r_L: the constraints admit no (r, L)        */
 } pdd_status;
 
 typedef void *pdd_stream; /* hipStream_t */
@@ -228,6 +229,47 @@ pdd_status pdd_select_sentences(const float *scores, int32_t n_heads, int32_t ba
                                 int32_t agg_mode, float *out_sent_scores,
                                 uint8_t *out_sent_keep, uint8_t *out_mask,
                                 int32_t *out_kept_tokens, pdd_stream stream);
+
+/*
+ * Aggregation of importance scores over attention layers and heads (Section
+ * 4.4: several attention layers take part, their weight magnitudes differ, and
+ * the layer strategy is left open; Section 3.2: scores are kept per head).
+ * The library computes one layer per call; this entry point combines layers:
+ *   out[h, j] = sum_l w_l * scores[l, h, j]              reduce_heads == 0
+ *   out[0, j] = sum_l w_l * sum_h scores[l, h, j]        reduce_heads != 0
+ * added to the previous contents of out when accumulate != 0 (streaming use:
+ * n_layers = 1 per finished layer).  fp32, layers then heads in ascending
+ * order.
+ *   scores        DEVICE fp32, layer l at scores + l * layer_stride, each
+ *                 [n_heads, total_k] contiguous                             -- in
+ *   layer_weights DEVICE fp32[n_layers] or NULL (all 1)                     -- in
+ *   out           DEVICE fp32 [reduce_heads ? 1 : n_heads, total_k]         -- out (in/out)
+ */
+pdd_status pdd_aggregate_scores(const float *scores, int32_t n_layers, int32_t n_heads,
+                                int32_t total_k, int64_t layer_stride,
+                                const float *layer_weights, int32_t reduce_heads,
+                                int32_t accumulate, float *out, pdd_stream stream);
+
+/*
+ * Refinement ratio r and early-termination length L (Section 3.5, program P:
+ * minimise the on-device TTFT subject to Eq. 5 on r and Eq. 6 on L; Section
+ * 4.2 observes that the optimum sits at L's lower bound).  Host-only scalar
+ * code, no GPU work.  With TTFT_c = k_c*l, prefill_d(x) = k_d*x and
+ * TTFT_d = k_c*l + delta + k_d*r*l the objective grows with r, so
+ *   r = xi_scene                     (must be <= 1 - (k_c + delta/l)/k_d, Eq. 5)
+ *   L = 1 + max(1, ceil((k_d*r*l - k_c*l) / (tau - tpot_d)))
+ *                                    (must satisfy L-1 <= (TTFT_d - TTFT_c)/tpot_c, Eq. 6)
+ * Returns PDD_ERR_INFEASIBLE when either range is empty; *r and *L are then
+ * left untouched.  Times in one unit throughout (k_* per token).
+ */
+typedef struct pdd_rl_model {
+    double k_c, k_d;       /* prefill time per prompt token: cloud, device      */
+    double delta;          /* bound on compress + decompress + RTT at length l  */
+    double xi_scene;       /* smallest ratio the scenario's quality allows      */
+    double tpot_c, tpot_d; /* time per output token: cloud, device              */
+    double tau;            /* largest tolerable smoothed TPOT                   */
+} pdd_rl_model;
+pdd_status pdd_choose_r_L(const pdd_rl_model *model, int32_t l, double *r, int32_t *L);
 
 /*
  * Mask -> bit stream (Section 3.2: the mask tensor is treated as a bit stream

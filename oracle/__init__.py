@@ -19,8 +19,10 @@ from .core import (
     pack_mask,
     pool_scores,
     select_sentences,
+    aggregate_scores,
+    choose_r_L,
     num_threads,
     widen_bf16,
 )
 
-__all__ = ["build", "attention", "importance", "select_topk", "pack_mask", "pool_scores", "select_sentences", "num_threads", "widen_bf16"]
+__all__ = ["build", "attention", "importance", "select_topk", "pack_mask", "pool_scores", "select_sentences", "aggregate_scores", "choose_r_L", "num_threads", "widen_bf16"]

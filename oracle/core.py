@@ -231,3 +231,44 @@ def select_sentences(scores, cu_k, cu_sent, sent_end, token_budget, mode="mean",
                 mask[g, cu_k[b] + starts[s]: cu_k[b] + ends[s]] = 1
             kept[g, b] = total
     return sscore, skeep, mask, kept
+
+
+def aggregate_scores(scores, weights=None, reduce_heads=False, acc=None):
+    """Weighted sum of per-layer importance scores [L, H, N] over layers, and over
+    heads when reduce_heads (Section 4.4: several attention layers take part in
+    the selection; the strategy is left open, so the weights are inputs).  fp64.
+    acc: previous contents of the output when accumulating."""
+    s = np.asarray(scores, dtype=np.float64)
+    w = np.ones(s.shape[0]) if weights is None else np.asarray(weights, dtype=np.float64)
+    out = np.zeros((1 if reduce_heads else s.shape[1], s.shape[2]))
+    for l in range(s.shape[0]):
+        for h in range(s.shape[1]):
+            out[0 if reduce_heads else h] += w[l] * s[l, h]
+    return out if acc is None else out + np.asarray(acc, dtype=np.float64)
+
+
+def choose_r_L(l, k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau, r_grid=2000, L_max=5000):
+    """Program P of Section 3.5 by exhaustive search: minimise
+    TTFT_d = k_c l + delta + k_d r l over a grid of ratios r in [0, 1] (the grid
+    contains xi_scene) and integers 2 <= L <= L_max, subject to Eq. 5
+    (xi_scene <= r <= 1 - (k_c + delta/l)/k_d) and Eq. 6
+    ((prefill_d(rl) - TTFT_c)/(tau - TPOT_d) <= L-1 <= (TTFT_d - TTFT_c)/TPOT_c).
+    Among minimisers the smallest L is returned (Section 4.2: the optimum is at
+    L's lower bound).  Returns (r, L) or None when nothing is feasible."""
+    best = None
+    rs = sorted(set([i / r_grid for i in range(r_grid + 1)] + [xi_scene]))
+    for r in rs:
+        if not (xi_scene <= r <= 1 - (k_c + delta / l) / k_d):
+            continue
+        ttft_c = k_c * l
+        ttft_d = k_c * l + delta + k_d * r * l
+        for L in range(2, L_max + 1):
+            smooth_ok = (k_d * r * l - ttft_c) <= (L - 1) * (tau - tpot_d)
+            cloud_ok = ttft_c + (L - 1) * tpot_c <= ttft_d
+            if smooth_ok and cloud_ok:
+                if best is None or ttft_d < best[0]:
+                    best = (ttft_d, r, L)
+                break                     # larger L never lowers TTFT_d for this r
+            if not cloud_ok:
+                break
+    return None if best is None else (best[1], best[2])

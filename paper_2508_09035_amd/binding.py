@@ -21,6 +21,12 @@ class PddError(RuntimeError):
         self.status = status
 
 
+class RLModel(ctypes.Structure):
+    """Mirror of pdd_rl_model."""
+    _fields_ = [(n, ctypes.c_double) for n in
+                ("k_c", "k_d", "delta", "xi_scene", "tpot_c", "tpot_d", "tau")]
+
+
 class AttnDesc(ctypes.Structure):
     """Mirror of `pdd_attn_desc`."""
     _fields_ = [
@@ -68,6 +74,11 @@ def load_library():
     lib.pdd_select_sentences.restype = ctypes.c_int
     lib.pdd_select_sentences.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, vp, i32, i32, vp, vp,
                                          i32, vp, vp, vp, vp, vp]
+    lib.pdd_aggregate_scores.restype = ctypes.c_int
+    lib.pdd_aggregate_scores.argtypes = [vp, i32, i32, i32, ctypes.c_int64, vp, i32, i32, vp, vp]
+    lib.pdd_choose_r_L.restype = ctypes.c_int
+    lib.pdd_choose_r_L.argtypes = [ctypes.POINTER(RLModel), i32, ctypes.POINTER(ctypes.c_double),
+                                   ctypes.POINTER(ctypes.c_int32)]
     lib.pdd_pack_mask.restype = ctypes.c_int
     lib.pdd_pack_mask.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, i32, vp, vp]
     lib.pdd_workspace_bytes.restype = sz
@@ -241,6 +252,26 @@ def select_sentences(scores, cu_seqlens_k, max_seqlen_k, cu_sent, sent_end, max_
         int(agg_mode), _ptr(out_sent_scores), _ptr(out_sent_keep), _ptr(out_mask),
         _ptr(out_kept_tokens), _stream()))
     del kh
+
+
+def aggregate_scores(scores, out, layer_weights=None, reduce_heads=False, accumulate=False):
+    """pdd_aggregate_scores: scores fp32 [n_layers, n_heads, total_k] (layers may be strided)
+    -> out fp32 [n_heads or 1, total_k], weighted sum over layers (and heads)."""
+    _check_tensors(scores, out, layer_weights)
+    if scores.dim() != 3 or scores.stride(2) != 1 or scores.stride(1) != scores.shape[2]:
+        raise ValueError("scores must be [n_layers, n_heads, total_k] with contiguous layers")
+    _check(load_library().pdd_aggregate_scores(
+        _ptr(scores), scores.shape[0], scores.shape[1], scores.shape[2], scores.stride(0),
+        _ptr(layer_weights), int(bool(reduce_heads)), int(bool(accumulate)), _ptr(out), _stream()))
+
+
+def choose_r_L(l, k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau):
+    """pdd_choose_r_L (host only): closed-form (r, L) of the paper's program P; raises PddError
+    when the constraints admit no solution."""
+    m = RLModel(k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau)
+    r, L = ctypes.c_double(), ctypes.c_int32()
+    _check(load_library().pdd_choose_r_L(ctypes.byref(m), int(l), ctypes.byref(r), ctypes.byref(L)))
+    return r.value, L.value
 
 
 def pack_mask(mask, cu_seqlens_k, max_seqlen_k, cu_bytes, total_bytes, out_bits,

@@ -15,6 +15,8 @@
 #include "select_topk.hpp"
 #include "pack_mask.hpp"
 #include "select_sentences.hpp"
+#include "aggregate.hpp"
+#include <cmath>
 
 namespace {
 
@@ -361,6 +363,60 @@ pdd_status pdd_select_sentences(const float *scores, int32_t n_heads, int32_t ba
                        dim3(pdd::kSelThreads), smem, (hipStream_t)stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(PDD_ERR_HIP, "sentence select launch: %s", hipGetErrorString(e));
+    return PDD_OK;
+}
+
+pdd_status pdd_aggregate_scores(const float *scores, int32_t n_layers, int32_t n_heads, int32_t total_k,
+                                int64_t layer_stride, const float *layer_weights, int32_t reduce_heads,
+                                int32_t accumulate, float *out, pdd_stream stream)
+{
+    if (!scores || !out) return fail(PDD_ERR_INVALID_ARG, "NULL pointer");
+    if (n_layers < 1 || n_heads < 1 || n_heads > 65535 || total_k < 0)
+        return fail(PDD_ERR_INVALID_ARG, "bad sizes");
+    if (layer_stride < (int64_t)n_heads * total_k)
+        return fail(PDD_ERR_INVALID_ARG, "layer_stride smaller than n_heads * total_k");
+    if (total_k == 0) return PDD_OK;
+    pdd::AggParams p;
+    p.scores = scores;  p.weights = layer_weights;  p.out = out;  p.layer_stride = layer_stride;
+    p.n_layers = n_layers;  p.n_heads = n_heads;  p.total_k = total_k;
+    p.reduce_heads = reduce_heads ? 1 : 0;  p.accumulate = accumulate ? 1 : 0;
+    const bool vec = total_k % 4 == 0 && layer_stride % 4 == 0 && ((uintptr_t)scores % 16) == 0 &&
+                     ((uintptr_t)out % 16) == 0;
+    const int per_block = 256 * (vec ? 4 : 1);
+    const dim3 grid((unsigned)((total_k + per_block - 1) / per_block), (unsigned)(reduce_heads ? 1 : n_heads));
+    if (vec) hipLaunchKernelGGL(pdd::aggregate_scores_kernel<4>, grid, dim3(256), 0, (hipStream_t)stream, p);
+    else     hipLaunchKernelGGL(pdd::aggregate_scores_kernel<1>, grid, dim3(256), 0, (hipStream_t)stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "aggregate launch: %s", hipGetErrorString(e));
+    return PDD_OK;
+}
+
+/* Host-only scalar code: the closed form of the program that picks (r, L). */
+pdd_status pdd_choose_r_L(const pdd_rl_model *m, int32_t l, double *r_out, int32_t *L_out)
+{
+    if (!m || !r_out || !L_out) return fail(PDD_ERR_INVALID_ARG, "NULL pointer");
+    if (l < 1) return fail(PDD_ERR_INVALID_ARG, "prompt length must be >= 1");
+    if (!(m->k_c >= 0) || !(m->k_d > 0) || !(m->delta >= 0) || !(m->tpot_c > 0) || !(m->tpot_d > 0) ||
+        !(m->xi_scene >= 0 && m->xi_scene <= 1))
+        return fail(PDD_ERR_INVALID_ARG, "model coefficients out of range");
+    if (!(m->tau > m->tpot_d)) return fail(PDD_ERR_INFEASIBLE, "tau must exceed the device TPOT");
+    const double len = (double)l;
+    /* the objective grows with r, so the smallest admissible ratio is optimal */
+    const double r = m->xi_scene;
+    const double r_max = 1.0 - (m->k_c + m->delta / len) / m->k_d;
+    if (r > r_max) return fail(PDD_ERR_INFEASIBLE, "no ratio in [xi_scene, %.6g]", r_max);
+    const double ttft_c = m->k_c * len;
+    const double prefill_d = m->k_d * r * len;
+    const double ttft_d = ttft_c + m->delta + prefill_d;
+    const double lo = (prefill_d - ttft_c) / (m->tau - m->tpot_d);
+    const double hi = (ttft_d - ttft_c) / m->tpot_c;
+    /* smallest integer L >= 2 with L - 1 >= lo */
+    double lm1 = std::ceil(lo);
+    if (lm1 < 1.0) lm1 = 1.0;
+    if (lm1 > hi) return fail(PDD_ERR_INFEASIBLE, "no L with %.6g <= L - 1 <= %.6g", lo, hi);
+    if (lm1 > 2147483646.0) return fail(PDD_ERR_INFEASIBLE, "L out of range");
+    *r_out = r;
+    *L_out = (int32_t)lm1 + 1;
     return PDD_OK;
 }
 

@@ -118,3 +118,31 @@ def test_importance_and_select_validation():
         pdd.set_option(pdd.OPT_ATTN_WAVES, 5)
     pdd.set_option(pdd.OPT_ATTN_WAVES, 0)
     assert pdd.workspace_bytes(good_desc(), 0) < 64 * 64 * 4     # never O(N^2)
+
+
+def test_choose_r_L_against_exhaustive_search():
+    """Host-only entry point: the closed form must agree with the oracle's search of program P."""
+    import oracle
+    rng = np.random.default_rng(5)
+    n_feasible = n_infeasible = 0
+    for _ in range(60):
+        c = dict(l=int(rng.integers(64, 40000)), k_c=float(rng.uniform(0.005, 0.2)),
+                 k_d=float(rng.uniform(0.1, 1.0)), delta=float(rng.uniform(0, 800)),
+                 xi_scene=float(rng.integers(1, 19)) / 20, tpot_c=float(rng.uniform(10, 60)),
+                 tpot_d=float(rng.uniform(30, 90)), tau=float(rng.uniform(95, 200)))
+        want = oracle.choose_r_L(**c)
+        if want is None:
+            with pytest.raises(pdd.PddError) as e:
+                pdd.choose_r_L(**c)
+            assert e.value.status == -5
+            n_infeasible += 1
+        else:
+            assert pdd.choose_r_L(**c) == want
+            n_feasible += 1
+    assert n_feasible >= 10 and n_infeasible >= 5
+    with pytest.raises(pdd.PddError) as e:
+        pdd.choose_r_L(0, 0.02, 0.5, 300, 0.6, 30, 50, 100)
+    assert e.value.status == -1
+    with pytest.raises(pdd.PddError) as e:                        # tau must exceed the device TPOT
+        pdd.choose_r_L(100, 0.02, 0.5, 300, 0.6, 30, 50, 50)
+    assert e.value.status == -5

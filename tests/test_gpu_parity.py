@@ -383,3 +383,32 @@ def test_select_sentences(mode, exact_scores):
             sl = slice(cu_sent[b], cu_sent[b + 1])
             others = np.delete(want_sc[g, sl], s - cu_sent[b])
             assert np.min(np.abs(others - want_sc[g, s])) <= 4e-6 * max(abs(want_sc[g, s]), 1e-30), (g, s)
+
+
+# --------------------------------------------------- cross-layer aggregation
+@pytest.mark.parametrize("total_k,reduce_heads", [(32768, False), (32768, True), (1003, False), (1003, True)])
+def test_aggregate_scores(total_k, reduce_heads):
+    rng = np.random.default_rng(17)
+    n_layers, heads = 6, 8
+    s32 = (rng.random((n_layers, heads, total_k)) ** 6).astype(np.float32)
+    w32 = rng.random(n_layers).astype(np.float32)
+    rows = 1 if reduce_heads else heads
+    want = oracle.aggregate_scores(s32, w32, reduce_heads)
+    out = torch.full((rows, total_k), float("nan"), dtype=torch.float32, device="cuda")
+    sd = torch.from_numpy(s32).cuda()
+    pdd.aggregate_scores(sd, out, torch.from_numpy(w32).cuda(), reduce_heads)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy().astype(np.float64), want, rtol=2e-6, atol=1e-12)
+    # unweighted, one layer at a time into the same buffer == all layers at once
+    out2 = torch.zeros((rows, total_k), dtype=torch.float32, device="cuda")
+    for l in range(n_layers):
+        pdd.aggregate_scores(sd[l:l + 1], out2, None, reduce_heads, accumulate=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out2.cpu().numpy().astype(np.float64),
+                               oracle.aggregate_scores(s32, None, reduce_heads), rtol=2e-6, atol=1e-12)
+    # a strided layer view (every second layer of the stack)
+    out3 = torch.empty((rows, total_k), dtype=torch.float32, device="cuda")
+    pdd.aggregate_scores(sd[::2], out3, None, reduce_heads)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out3.cpu().numpy().astype(np.float64),
+                               oracle.aggregate_scores(s32[::2], None, reduce_heads), rtol=2e-6, atol=1e-12)

@@ -420,3 +420,42 @@ def test_select_sentences_reduces_to_token_topk_and_invariants():
         if (keep[0] == 0).any():
             best_dropped = np.flatnonzero(keep[0] == 0)[np.argmax(sc[0][keep[0] == 0])]
             assert kept[0, 0] + ln[best_dropped] > 120
+
+
+# ------------------------------------- cross-layer aggregation, (r, L) chooser
+def test_aggregate_scores_pins():
+    s = np.arange(2 * 3 * 4, dtype=np.float64).reshape(2, 3, 4)
+    # hand values: layer 0 rows 0..11, layer 1 rows 12..23
+    got = oracle.aggregate_scores(s, [1.0, 0.5])
+    assert got.tolist() == [[6, 7.5, 9, 10.5], [12, 13.5, 15, 16.5], [18, 19.5, 21, 22.5]]
+    got = oracle.aggregate_scores(s, [1.0, 0.5], reduce_heads=True)
+    assert got.tolist() == [[36, 40.5, 45, 49.5]]
+    rng = np.random.default_rng(0)
+    x = rng.random((5, 4, 33)); w = rng.random(5)
+    np.testing.assert_allclose(oracle.aggregate_scores(x, w), np.einsum("l,lhn->hn", w, x), rtol=1e-14)
+    np.testing.assert_allclose(oracle.aggregate_scores(x, None, True), x.sum((0, 1))[None], rtol=1e-14)
+    one_hot = np.zeros(5); one_hot[3] = 1
+    assert np.array_equal(oracle.aggregate_scores(x, one_hot), x[3])
+    acc = rng.random((4, 33))
+    np.testing.assert_allclose(oracle.aggregate_scores(x, w, acc=acc), acc + np.einsum("l,lhn->hn", w, x), rtol=1e-14)
+
+
+def test_choose_r_L_search_matches_closed_form():
+    # the objective grows with r, so r* = xi_scene whenever Eq. 5 leaves room; L* = the smallest
+    # integer >= 2 meeting the smoothed-TPOT bound, valid only below the cloud-occupation bound
+    import math
+    cases = [dict(l=8192, k_c=0.02, k_d=0.5, delta=300, xi_scene=0.6, tpot_c=30, tpot_d=50, tau=100),
+             dict(l=4096, k_c=0.05, k_d=0.4, delta=150, xi_scene=0.25, tpot_c=20, tpot_d=40, tau=100),
+             dict(l=32768, k_c=0.01, k_d=0.3, delta=500, xi_scene=0.5, tpot_c=25, tpot_d=60, tau=120),
+             dict(l=100, k_c=0.3, k_d=0.5, delta=5, xi_scene=0.2, tpot_c=10, tpot_d=50, tau=100)]
+    for c in cases:
+        got = oracle.choose_r_L(**c)
+        lo = (c["k_d"] * c["xi_scene"] * c["l"] - c["k_c"] * c["l"]) / (c["tau"] - c["tpot_d"])
+        assert got is not None
+        assert got[0] == c["xi_scene"] and got[1] == 1 + max(1, math.ceil(lo))
+    # worked numbers for the first case: prefill_d = 2457.6, TTFT_c = 163.84 -> (2293.76 / 50) = 45.9 -> L = 47
+    assert oracle.choose_r_L(**cases[0]) == (0.6, 47)
+    # Eq. 5 empty: the cloud is too slow relative to the device
+    assert oracle.choose_r_L(8192, 0.4, 0.5, 300, 0.6, 30, 50, 100) is None
+    # Eq. 6 empty: the smoothing needs more cloud tokens than the occupation bound allows
+    assert oracle.choose_r_L(8192, 0.02, 0.5, 300, 0.6, 300, 50, 60) is None
