@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--config", default="c4", help="workload: c1..c5 (default: the 32k-token prompt)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--waves", type=int, default=0, help="attention waves per workgroup (0 = auto)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="after the timed legs also run one plain device copy of this many MiB "
+                         "(a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -95,6 +98,13 @@ def main():
     ms_attn = time_gpu(lambda: dev.attn(with_importance=False), args.steps, 2)
     ms_attn_imp = time_gpu(lambda: dev.attn(with_importance=True), args.steps, 2)
     ms_select = time_gpu(dev.select, args.steps, 2)
+
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     attn_flops, imp_flops = wl.attn_flops(), wl.importance_flops()
     tflops_path = (attn_flops + imp_flops) / (ms_step * 1e-3) / 1e12

@@ -63,13 +63,23 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t *)p;
 }
 
-__device__ __forceinline__ bf16x8 lds_read_tr8(const uint8_t *lo, const uint8_t *hi)
+__device__ __forceinline__ bf16x8 lds_read_tr8(uint32_t lo, uint32_t hi)
 {
-    // two transposing 64-bit reads -> 8 bf16 (k-slots 0..3 from lo, 4..7 from hi)
-    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)lo);
-    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)hi);
+    // two transposing 64-bit reads -> 8 bf16 (k-slots 0..3 from lo, 4..7 from hi); lo / hi are
+    // LDS byte addresses, so that constant parts fold into the instruction's offset field
+    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(uintptr_t)lo);
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(uintptr_t)hi);
     const s16x8 c = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, c);
+}
+
+// max(m, x of this lane, x of the lane 32 positions away): after the swap of (x, x) the first
+// result holds the lower half's values in both halves and the second the upper half's
+__device__ __forceinline__ float max_with_other_half(float m, float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return max3(m, __uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 template <int NWAVES>
@@ -172,7 +182,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
                 const int chunk = 4 * db + 2 * dhalf + ((s16 & 3) >> 1);
-                vaddr[db][eg] = (uint32_t)row * 256u + (uint32_t)((chunk ^ swz16(row)) * 16) + 8u * (s16 & 1);
+                vaddr[db][eg] = vs_lds + (uint32_t)row * 256u + (uint32_t)((chunk ^ swz16(row)) * 16) + 8u * (s16 & 1);
             }
         }
     }
@@ -182,8 +192,10 @@ void attn_fwd_d128_kernel(const AttnParams p)
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY;
+    float l_part[4] = {0.f, 0.f, 0.f, 0.f};   // four interleaved partial row sums (short add chains)
     const float c2 = p.scale_log2;
+    float neg_mc = 0.f;                        // -m_run * c2 (0 while m_run is -inf)
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // S^T of the 32-key block at byte offset `koff` of the K buffers
@@ -197,37 +209,37 @@ void attn_fwd_d128_kernel(const AttnParams p)
     };
 
     // short dependency chains: a 3-level tree of v_max3 instead of one serial chain
+    // max(m_run, row max of s): the query's keys are spread over this lane and lane ^ 32
     auto row_max = [&](const f32x16 &s) {
         const float t0 = max3(s[0], s[1], s[2]), t1 = max3(s[4], s[5], s[6]);
         const float t2 = max3(s[8], s[9], s[10]), t3 = max3(s[12], s[13], s[14]);
         const float u0 = max3(t0, t1, s[3]), u1 = max3(t2, t3, s[7]);
         const float tmax = max3(max3(u0, u1, s[11]), s[15], s[15]);
-        return fmaxf(tmax, xchg_half(tmax));
+        return max_with_other_half(m_run, tmax);
     };
 
     auto rescale = [&](float m_new) {
         const float alpha = (m_run == -INFINITY) ? 0.f : fast_exp2((m_run - m_new) * c2);
-        l_run *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) l_part[i] *= alpha;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
         m_run = m_new;
+        neg_mc = (m_new == -INFINITY) ? 0.f : -m_new * c2;
     };
 
-    auto exp_block = [&](f32x16 &s, float mc) {
-        float ps[4] = {0.f, 0.f, 0.f, 0.f};    // four independent partial sums
+    auto exp_block = [&](f32x16 &s) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            s[e] = fast_exp2(fmaf(s[e], c2, -mc));
-            ps[e & 3] += s[e];
+            s[e] = fast_exp2(fmaf(s[e], c2, neg_mc));
+            l_part[e & 3] += s[e];
         }
-        l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
     };
 
     // O^T += V^T P^T for the 32-key block at byte offset `voff` of the V buffers
     auto pv_block = [&](uint32_t voff, const f32x16 &s) {
-        const uint8_t *vb = Vs + voff;
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
             f32x8 pf;
@@ -236,7 +248,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
             const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
-                const bf16x8 a = lds_read_tr8(vb + 4096 * st + vaddr[db][0], vb + 4096 * st + vaddr[db][1]);
+                const bf16x8 a = lds_read_tr8(vaddr[db][0] + voff + 4096 * st, vaddr[db][1] + voff + 4096 * st);
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
             }
         }
@@ -265,30 +277,58 @@ void attn_fwd_d128_kernel(const AttnParams p)
     n_hot = max(0, min(n_hot, n_tiles - 1));
     n_hot -= n_hot % 3;
 
-    // `m_cand` carries the row max of `cur` (computed one block earlier, while the
-    // previous PV MFMAs were running) so that the exponentials never wait for a max.
-    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, float &m_cand, uint32_t k_next, uint32_t v_cur) {
-        const float m_new = fmaxf(m_run, m_cand);
-        if (__any(m_new > m_run)) rescale(m_new);
-        const float mc = m_run * c2;
-        qk_block(k_next, nxt);
-        exp_block(cur, mc);
-        pv_block(v_cur, cur);
+    // `m_cand` carries max(m_run, row max of `cur`), computed one block earlier while the
+    // previous PV MFMAs were running, so that the exponentials never wait for a max.  LDS
+    // fragment reads are issued a phase ahead of the MFMAs that consume them: the V^T
+    // fragments of `cur` before the QK MFMAs of `nxt`, the K fragments of the block after
+    // `nxt` (`kf`) before the PV MFMAs of `cur`.
+    bf16x8 kf[NKK];
+    auto load_kf = [&](uint32_t koff) {
+        const uint8_t *kb = Ks + koff;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) kf[kk] = *(const bf16x8 *)(kb + kaddr[kk]);
+    };
+    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, float &m_cand, uint32_t k_next2, uint32_t v_cur) {
+        if (__any(m_cand > m_run)) rescale(m_cand);
+        bf16x8 vf[2][NDB];
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+                vf[st][db] = lds_read_tr8(vaddr[db][0] + v_cur + 4096 * st, vaddr[db][1] + v_cur + 4096 * st);
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+            nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], kk == 0 ? zero16 : nxt, 0, 0, 0);
+        exp_block(cur);
+        __builtin_amdgcn_sched_barrier(0);
+        load_kf(k_next2);
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            f32x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = cur[8 * st + e];
+            const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pb, oacc[db], 0, 0, 0);
+        }
         m_cand = row_max(nxt);
+        __builtin_amdgcn_sched_barrier(0);
     };
     auto hot_tile = [&](auto par_c, const int it, float &m_cand) {
         constexpr int PAR = decltype(par_c)::value;
         constexpr int P1 = (PAR + 1) % 3, P2 = (PAR + 2) % 3;
         issue_v(it + 1, P1);
         if (it + 2 < n_tiles) issue_k(it + 2, P2);
-        hot_half(sA, sB, m_cand, PAR * kTileBytes + 32 * 256, PAR * kTileBytes);
-        hot_half(sB, sA, m_cand, P1 * kTileBytes, PAR * kTileBytes + 2 * 4096);
+        hot_half(sA, sB, m_cand, P1 * kTileBytes, PAR * kTileBytes);
+        hot_half(sB, sA, m_cand, P1 * kTileBytes + 32 * 256, PAR * kTileBytes + 2 * 4096);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };
     int it = 0;
     if (n_hot > 0) {
         float m_cand = row_max(sA);
+        load_kf(32 * 256);
         for (; it < n_hot; it += 3) {
             hot_tile(std::integral_constant<int, 0>{}, it, m_cand);
             hot_tile(std::integral_constant<int, 1>{}, it + 1, m_cand);
@@ -310,10 +350,9 @@ void attn_fwd_d128_kernel(const AttnParams p)
                     if (j > lim) cur[e] = -INFINITY;
                 }
             }
-            const float m_new = fmaxf(m_run, row_max(cur));
+            const float m_new = row_max(cur);
             if (__any(m_new > m_run)) rescale(m_new);
-            const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
-            exp_block(cur, mc);
+            exp_block(cur);
             pv_block(v_cur, cur);
         }
     };
@@ -328,6 +367,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
     }
 
     // ---- epilogue
+    const float l_run = (l_part[0] + l_part[1]) + (l_part[2] + l_part[3]);
     const float l_tot = l_run + xchg_half(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (qrow < nq) {
