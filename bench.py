@@ -19,6 +19,21 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the attention kernel (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc runs, each
+# scaled by the same counter's reading for a 1 GiB device copy; see profiles/).  Valid only for the
+# kernel sources with this digest: once they change the figure is reported as null.
+KERNEL_SOURCES = ("attn_fwd_d128.hpp", "attn_fwd.hpp")
+TRAFFIC = {"c4": {"bytes": 1.679e9, "sources_sha256": "30271cac1cb574fecfe56b7d95da300022128c800ceb941a004cefc25009506a"}}
+
+
+def kernel_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2508_09035_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
 
 def time_gpu(fn, iters, warmup):
     import torch
@@ -71,10 +86,15 @@ def main():
     ap.add_argument("--config", default="c4", help="workload: c1..c5 (default: the 32k-token prompt)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--waves", type=int, default=0, help="attention waves per workgroup (0 = auto)")
+    ap.add_argument("--kernel-digest", action="store_true", help="print the digest of the attention "
+                    "kernel sources (the key of the stored HBM traffic figure) and exit")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed legs also run one plain device copy of this many MiB "
                          "(a known-size reference for HBM byte counters)")
     args = ap.parse_args()
+    if args.kernel_digest:
+        print(kernel_digest())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
@@ -111,6 +131,8 @@ def main():
     tflops_attn = attn_flops / (ms_attn * 1e-3) / 1e12
     sel_bytes = 4 * wl.n_kv_heads * int((wl.cand_end - wl.cand_begin).sum()) \
         + 4 * wl.n_kv_heads * int(wl.k_keep.sum()) + wl.n_kv_heads * wl.total_k
+    t = TRAFFIC.get(wl.name)
+    traffic = t["bytes"] if t and t["sources_sha256"] == kernel_digest() else None
     out = {
         "metric": "causal prefill attn TFLOP/s (+importance) & % bf16 MFMA peak; prompt tokens/s",
         "value": round(tflops_path, 2),
@@ -132,7 +154,7 @@ def main():
                      "kernel": "attn_fwd_d128_kernel" if wl.head_dim == 128 else "attn_fwd_kernel",
                      "achieved": round(tflops_attn, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None},
+                     "traffic": traffic},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
@@ -147,4 +169,6 @@ if __name__ == "__main__":
 #                  4*d per visible pair + 2*d per window pair) / step time
 #   roofline       the attention kernel alone: algorithmic flops per launch / its
 #                  average duration between HIP events, against the dense bf16 MFMA peak
+#                  traffic = HBM bytes per launch from byte counters (null when not measured for
+#                  these kernel sources)
 #   cpu_baseline   the fp64 oracle timed on a bounded sample of rows (reported, not a target)
