@@ -12,8 +12,10 @@
 // fragments stay in registers as B operands for the whole kernel).  The window
 // rows of the G query heads are streamed through LDS in blocks of 32 rows
 // (buffer_load ... lds, double buffered, swizzled like the attention K tile)
-// together with their log-sum-exp values, so every Q fragment read from LDS
-// feeds two MFMAs and every Q row is fetched from L2 once per workgroup.
+// together with their log-sum-exp values (four buffers, three blocks in flight:
+// with little arithmetic per block the kernel lives on hiding the load latency),
+// so every Q fragment read from LDS feeds two MFMAs and every Q row is fetched
+// from L2 once per workgroup.
 // S = Q K^T puts key (l % 32) in lane l and 16 query rows in its accumulator
 // registers, so the sum over queries is in-lane; no atomics, fixed summation
 // order, deterministic.
@@ -35,9 +37,27 @@ struct ImpParams {
 
 constexpr int kImpWaves = 4;
 constexpr int kImpBK = 64 * kImpWaves;  // keys per workgroup
+constexpr int kImpBufs = 4;             // LDS ring of query-row blocks
+constexpr int kImpAhead = 3;            // blocks in flight
+
+// 4 bytes per lane from the buffer into LDS at lds_addr + 4 * lane (see dma16_to_lds)
+__device__ __forceinline__ void dma4_to_lds(i32x4 rsrc, uint32_t lds_addr, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
 
 template <int D>
-__global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpParams p)
+__global__ __launch_bounds__(kImpWaves * 64) __attribute__((amdgpu_waves_per_eu(3, 4)))
+void importance_kernel(const ImpParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int NKK = D / 16;
@@ -45,8 +65,9 @@ __global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpPar
     constexpr int CH = D / 8;                    // 16-byte chunks per row
     constexpr int QBLK_BYTES = 32 * ROW_BYTES;   // one block of 32 query rows
     constexpr int NLD = QBLK_BYTES / (kImpWaves * 1024);   // DMA instructions per block per wave (2 or 1)
-    __shared__ __attribute__((aligned(1024))) uint8_t qs_lds[2][QBLK_BYTES];
-    __shared__ __attribute__((aligned(16))) float lse_lds[2][32];
+    constexpr int PER_ITEM = NLD + 1;            // DMA instructions per block per wave (Q rows + LSE)
+    __shared__ __attribute__((aligned(1024))) uint8_t qs_lds[kImpBufs][QBLK_BYTES];
+    __shared__ __attribute__((aligned(256))) float lse_lds[kImpBufs][kImpWaves][64];   // a private copy per wave
 
     int bid = blockIdx.x;
     const int g = bid % p.Hkv;  bid /= p.Hkv;
@@ -92,7 +113,9 @@ __global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpPar
         const uint32_t q_row_bytes = (uint32_t)p.q_st * 2u;
         const uint32_t q_span = (uint32_t)(nq - 1) * q_row_bytes + (uint32_t)p.Hq * (uint32_t)p.q_sh * 2u;
         const i32x4 rsQ = make_rsrc(qbase, q_span);
+        const i32x4 rsL = make_rsrc(p.lse, (uint32_t)p.Hq * (uint32_t)p.total_q * 4u);
         const uint32_t q_lds = lds_addr_of(&qs_lds[0][0]);
+        const uint32_t l_lds = lds_addr_of(&lse_lds[0][wave][0]);
         // lane -> (row in block, chunk position); LDS chunk position holds chunk pos ^ swizzle(row)
         uint32_t qvoff[NLD];
         int qrow_l[NLD];
@@ -114,10 +137,8 @@ __global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpPar
                 dma16_to_lds(rsQ, q_lds + buf * QBLK_BYTES + 1024 * (wave + kImpWaves * ci),
                              (uint32_t)i * q_row_bytes + (uint32_t)h * (uint32_t)p.q_sh * 2u + qvoff[ci]);
             }
-            if (tid < 32) {
-                const int i = min(i0 + tid, nq - 1);
-                lse_lds[buf][tid] = p.lse[(int64_t)h * p.total_q + qs + i] * kLog2e;
-            }
+            const int il = min(i0 + (lane & 31), nq - 1);
+            dma4_to_lds(rsL, l_lds + buf * (kImpWaves * 256), ((uint32_t)h * (uint32_t)p.total_q + (uint32_t)(qs + il)) * 4u);
         };
         // A-operand read address of row n, chunk 2 kk + hh
         uint32_t qaddr[NKK];
@@ -128,12 +149,19 @@ __global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpPar
             qaddr[kk] = (uint32_t)n * ROW_BYTES + (uint32_t)cs * 16u;
         }
 
-        if (n_items > 0) issue_item(0, 0);
+        // the K fragment loads end here: the compiler then places no load waits inside the loop,
+        // where they would also wait for the asynchronous row-block transfers in flight
         __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
+        for (int i = 0; i < kImpAhead && i < n_items; ++i) issue_item(i, i);
         for (int item = 0; item < n_items; ++item) {
-            const int buf = item & 1;
-            if (item + 1 < n_items) issue_item(item + 1, buf ^ 1);
+            const int buf = item & (kImpBufs - 1);
+            // this block's loads are done once at most the blocks issued after it are outstanding
+            const int newer = min(kImpAhead - 1, n_items - 1 - item);
+            if (newer == 2) wait_vmcnt<2 * PER_ITEM>();
+            else if (newer == 1) wait_vmcnt<PER_ITEM>();
+            else wait_vmcnt<0>();
+            __syncthreads();     // every wave's part of the block has landed; the buffer refilled below is free
+            if (item + kImpAhead < n_items) issue_item(item + kImpAhead, (item + kImpAhead) & (kImpBufs - 1));
             const int rb = rb_first + item % (n_rb - rb_first);
             const int i0 = iw0 + 32 * rb;
             const int i_last = min(i0 + 31, nq - 1);
@@ -150,7 +178,7 @@ __global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpPar
                 // log2-domain LSE of rows 8 (e/4) + 4 hh + (e%4)
                 f32x4 l2[4];
 #pragma unroll
-                for (int bq = 0; bq < 4; ++bq) l2[bq] = *(const f32x4 *)&lse_lds[buf][8 * bq + 4 * hh];
+                for (int bq = 0; bq < 4; ++bq) l2[bq] = *(const f32x4 *)&lse_lds[buf][wave][8 * bq + 4 * hh] * kLog2e;
                 // rows beyond the sequence end or keys beyond a row's reach contribute nothing
                 const bool partial = (i0 + 31 > nq - 1) || (jw0 + 63 > i0 + delta) || (jw0 + 63 > nk - 1);
                 if (!partial) {
@@ -170,8 +198,6 @@ __global__ __launch_bounds__(kImpWaves * 64) void importance_kernel(const ImpPar
                     }
                 }
             }
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
         }
     }
 #pragma unroll

@@ -173,6 +173,8 @@ pdd_status launch_importance(const pdd_attn_desc *d, const void *q, const void *
     {   // 32-bit byte offsets inside one sequence's Q rows (buffer addressing)
         const int64_t span = 2 * ((int64_t)d->max_seqlen_q * d->q_stride_tok + (int64_t)d->n_q_heads * d->q_stride_head);
         if (span >= (1LL << 32)) return fail(PDD_ERR_UNSUPPORTED, "a sequence's Q span must stay below 4 GiB");
+        if ((int64_t)d->n_q_heads * d->total_q * 4 >= (1LL << 32))
+            return fail(PDD_ERR_UNSUPPORTED, "the log-sum-exp tensor must stay below 4 GiB");
     }
     const int64_t blocks = (int64_t)p.n_ktiles * d->batch * d->n_kv_heads;
     if (blocks > 0x7fffffffLL) return fail(PDD_ERR_INVALID_ARG, "launch grid too large");
