@@ -146,3 +146,34 @@ def test_choose_r_L_against_exhaustive_search():
     with pytest.raises(pdd.PddError) as e:                        # tau must exceed the device TPOT
         pdd.choose_r_L(100, 0.02, 0.5, 300, 0.6, 30, 50, 50)
     assert e.value.status == -5
+
+
+def test_refinement_entry_points_validation():
+    """Pooled selection, sentence selection, bit packing, aggregation: bad arguments are
+    rejected on the host before anything is launched."""
+    lib = pdd.load_library()
+    pooled = lambda kernel, mode: lib.pdd_select_topk_pooled(
+        0x1000, 2, 1, 64, 0x2000, None, 64, None, None, 0x3000, 0x4000, 8, kernel, mode, None,
+        0x5000, None, None, 0, None)
+    assert pooled(4, 1) == -1                      # even kernel
+    assert pooled(3, 7) == -1                      # unknown mode
+    sent = lambda **kw: lib.pdd_select_sentences(
+        kw.get("scores", 0x1000), 2, 1, 64, 0x2000, None, 64, kw.get("cu_sent", 0x3000),
+        kw.get("sent_end", 0x4000), kw.get("total_sent", 10), kw.get("max_sent", 10), None,
+        kw.get("budget", 0x5000), kw.get("mode", 0), None, 0x6000, 0x7000, None, None)
+    assert sent(scores=None) == -1
+    assert sent(budget=None) == -1
+    assert sent(mode=2) == -1
+    assert sent(max_sent=11) == -1                 # more per sequence than in total
+    assert sent(total_sent=20000, max_sent=9000) == -2 and "8192" in lib.pdd_last_error().decode()
+    pack = lambda **kw: lib.pdd_pack_mask(kw.get("mask", 0x1000), 2, 1, 64, 0x2000, None,
+                                          kw.get("max_k", 64), 0x3000, 8, kw.get("out", 0x4000), None)
+    assert pack(mask=None) == -1
+    assert pack(out=None) == -1
+    assert pack(max_k=65) == -1
+    agg = lambda **kw: lib.pdd_aggregate_scores(kw.get("scores", 0x1000), kw.get("layers", 2), 4, 64,
+                                                kw.get("stride", 256), None, 0, 0, kw.get("out", 0x2000), None)
+    assert agg(scores=None) == -1
+    assert agg(out=None) == -1
+    assert agg(layers=0) == -1
+    assert agg(stride=255) == -1 and "layer_stride" in lib.pdd_last_error().decode()
