@@ -38,7 +38,7 @@ extern "C" {
 typedef enum pdd_status {
     PDD_OK = 0,
     PDD_ERR_INVALID_ARG = -1, /* null pointer, bad size, Hq % Hkv != 0, misaligned, ... */
-    PDD_ERR_UNSUPPORTED = -2, /* head_dim not in {64, 128}                             */
+    PDD_ERR_UNSUPPORTED = -2, /* head_dim not in {64, 128}; a size beyond a documented limit */
     PDD_ERR_WORKSPACE = -3,   /* workspace smaller than pdd_workspace_bytes()           */
     PDD_ERR_HIP = -4,         /* a HIP runtime call (launch) reported an error          */
     PDD_ERR_INFEASIBLE = -5   /* pdd_choose_r_L: the constraints admit no (r, L)        */
@@ -110,6 +110,11 @@ enum {
  *            PDD_CALL_PREFILL_ATTN) bytes (may be NULL when that is 0).
  * Requires Nq_b == Nk_b for every sequence when host copies are given (use the
  * chunked entry point otherwise).
+ * Limits (PDD_ERR_UNSUPPORTED beyond them; the kernels address with 32-bit byte
+ * offsets): for head_dim 128 the K and V rows of one sequence,
+ * (max_seqlen_k + 64) * stride_tok * 2 bytes, must span less than 4 GiB; with
+ * an importance output the same holds for one sequence's Q rows and for the
+ * whole lse tensor (Hq * total_q * 4 bytes).
  */
 pdd_status pdd_prefill_attn(const pdd_attn_desc *desc, const void *q, const void *k,
                             const void *v, void *o, float *lse, float *importance,
