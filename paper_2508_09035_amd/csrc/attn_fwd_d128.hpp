@@ -138,7 +138,6 @@ void attn_fwd_d128_kernel(const AttnParams p)
     const uint32_t k_row_bytes = (uint32_t)p.k_st * 2u, v_row_bytes = (uint32_t)p.v_st * 2u;
     const uint32_t k_span = nk > 0 ? (uint32_t)(nk - 1) * k_row_bytes + 256u : 0u;
     const uint32_t v_span = nk > 0 ? (uint32_t)(nk - 1) * v_row_bytes + 256u : 0u;
-    const i32x4 rsK = make_rsrc(kbase, k_span), rsV = make_rsrc(vbase, v_span);
     const uint32_t ks_lds = lds_addr_of(Ks), vs_lds = lds_addr_of(Vs);
 
     // DMA lane mapping: instruction ci of wave w fills LDS rows 4q..4q+3, q = w + NWAVES*ci;
@@ -151,18 +150,23 @@ void attn_fwd_d128_kernel(const AttnParams p)
         kvoff[ci] = (uint32_t)r * k_row_bytes + (uint32_t)c * 16u;
         vvoff[ci] = (uint32_t)r * v_row_bytes + (uint32_t)c * 16u;
     }
+    // The tile's offset goes into the descriptor (scalar arithmetic): base advanced by the tile,
+    // num_records reduced by the same amount, so that the range check still ends at the sequence's
+    // last row and the per-lane offsets stay constant.
+    auto tile_rsrc = [&](const uint16_t *base, uint32_t span, uint32_t so) {
+        return make_rsrc((const uint8_t *)base + so, span > so ? span - so : 0u);
+    };
     auto issue_k = [&](int tile, int buf) {
-        // the tile offset goes into the per-lane offset: only that one is range checked
-        const uint32_t so = (uint32_t)tile * kBN * k_row_bytes;
+        const i32x4 rs = tile_rsrc(kbase, k_span, (uint32_t)tile * kBN * k_row_bytes);
 #pragma unroll
         for (int ci = 0; ci < NLD; ++ci)
-            dma16_to_lds(rsK, ks_lds + buf * kTileBytes + 1024 * (wave + NWAVES * ci), kvoff[ci] + so);
+            dma16_to_lds(rs, ks_lds + buf * kTileBytes + 1024 * (wave + NWAVES * ci), kvoff[ci]);
     };
     auto issue_v = [&](int tile, int buf) {
-        const uint32_t so = (uint32_t)tile * kBN * v_row_bytes;
+        const i32x4 rs = tile_rsrc(vbase, v_span, (uint32_t)tile * kBN * v_row_bytes);
 #pragma unroll
         for (int ci = 0; ci < NLD; ++ci)
-            dma16_to_lds(rsV, vs_lds + buf * kTileBytes + 1024 * (wave + NWAVES * ci), vvoff[ci] + so);
+            dma16_to_lds(rs, vs_lds + buf * kTileBytes + 1024 * (wave + NWAVES * ci), vvoff[ci]);
     };
 
     // ---- LDS read addresses (bytes inside a tile)
