@@ -292,7 +292,10 @@ void attn_fwd_d128_kernel(const AttnParams p)
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) kf[kk] = *(const bf16x8 *)(kb + kaddr[kk]);
     };
+    // The wave runs at raised issue priority while it has the exponentials to do and at normal
+    // priority during its PV MFMAs (measured: 1 % on the 32k prompt, 3 % on constant inputs).
     auto hot_half = [&](f32x16 &cur, f32x16 &nxt, float &m_cand, uint32_t k_next2, uint32_t v_cur) {
+        __builtin_amdgcn_s_setprio(1);
         if (__any(m_cand > m_run)) rescale(m_cand);
         bf16x8 vf[2][NDB];
 #pragma unroll
@@ -305,6 +308,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
             nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], kk == 0 ? zero16 : nxt, 0, 0, 0);
         exp_block(cur);
         __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(0);
         load_kf(k_next2);
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
