@@ -177,3 +177,14 @@ def test_refinement_entry_points_validation():
     assert agg(out=None) == -1
     assert agg(layers=0) == -1
     assert agg(stride=255) == -1 and "layer_stride" in lib.pdd_last_error().decode()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only; asking for more exits with a message instead of a JSON line."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
