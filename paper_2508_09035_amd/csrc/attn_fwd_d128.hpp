@@ -273,13 +273,12 @@ void attn_fwd_d128_kernel(const AttnParams p)
     f32x16 sA = zero16, sB = zero16;
     if (n_tiles > 0) qk_block(0, sA);   // block 0 is visible to every wave
 
-    // ---- hot loop: tiles that no wave of the workgroup has to mask and whose
-    // successor is fully visible to all of them: no per-wave branches at all.
-    //   need: 64 (t+2) - 1 <= m0 + delta  (first query of the workgroup)
+    // ---- hot loop: tiles that no wave of the workgroup has to mask (fully visible to the
+    // workgroup's first query: 64 (t+1) - 1 <= m0 + delta) and that have a successor tile: no
+    // per-wave branches at all.  The scores the last hot tile computes ahead for the first
+    // block of the next (diagonal) tile are masked by the generic loop before they are used.
     const int first_lim = m0 + delta;
-    int n_hot = (first_lim + 1) / kBN - 1;           // tiles 0 .. n_hot-1 qualify
-    n_hot = max(0, min(n_hot, n_tiles - 1));
-    n_hot -= n_hot % 3;
+    const int n_hot = max(0, min((first_lim + 1) / kBN, n_tiles - 1));   // tiles 0 .. n_hot-1
 
     // `m_cand` carries max(m_run, row max of `cur`), computed one block earlier while the
     // previous PV MFMAs were running, so that the exponentials never wait for a max.  LDS
@@ -337,11 +336,13 @@ void attn_fwd_d128_kernel(const AttnParams p)
     if (n_hot > 0) {
         float m_cand = row_max(sA);
         load_kf(32 * 256);
-        for (; it < n_hot; it += 3) {
+        for (; it + 3 <= n_hot; it += 3) {          // unrolled over the three LDS buffers
             hot_tile(std::integral_constant<int, 0>{}, it, m_cand);
             hot_tile(std::integral_constant<int, 1>{}, it + 1, m_cand);
             hot_tile(std::integral_constant<int, 2>{}, it + 2, m_cand);
         }
+        if (it < n_hot) { hot_tile(std::integral_constant<int, 0>{}, it, m_cand); ++it; }
+        if (it < n_hot) { hot_tile(std::integral_constant<int, 1>{}, it, m_cand); ++it; }
     }
 
     // ---- remaining tiles (the diagonal region): per-wave activity and masking
