@@ -306,7 +306,6 @@ void attn_fwd_d128_kernel(const AttnParams p)
         for (int kk = 0; kk < NKK; ++kk)
             nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], kk == 0 ? zero16 : nxt, 0, 0, 0);
         exp_block(cur);
-        __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(0);
         load_kf(k_next2);
 #pragma unroll
@@ -320,7 +319,6 @@ void attn_fwd_d128_kernel(const AttnParams p)
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pb, oacc[db], 0, 0, 0);
         }
         m_cand = row_max(nxt);
-        __builtin_amdgcn_sched_barrier(0);
     };
     auto hot_tile = [&](auto par_c, const int it, float &m_cand) {
         constexpr int PAR = decltype(par_c)::value;
