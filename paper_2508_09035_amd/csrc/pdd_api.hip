@@ -439,7 +439,7 @@ pdd_status pdd_pack_mask(const uint8_t *mask, int32_t n_rows, int32_t batch, int
     p.mask = mask;  p.bits = out_bits;  p.cu_k = cu_seqlens_k;  p.cu_bytes = cu_bytes;
     p.rows = n_rows;  p.B = batch;  p.total_k = total_k;  p.total_bytes = total_bytes;
     const int max_bytes = (max_seqlen_k + 7) / 8;
-    const unsigned gx = (unsigned)((8 * max_bytes + pdd::kPackThreads - 1) / pdd::kPackThreads);
+    const unsigned gx = (unsigned)((max_bytes + pdd::kPackThreads - 1) / pdd::kPackThreads);
     hipLaunchKernelGGL(pdd::pack_mask_kernel, dim3(gx, (unsigned)batch, (unsigned)n_rows), dim3(pdd::kPackThreads), 0,
                        (hipStream_t)stream, p);
     const hipError_t e = hipGetLastError();
