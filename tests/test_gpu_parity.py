@@ -412,3 +412,66 @@ def test_aggregate_scores(total_k, reduce_heads):
     torch.cuda.synchronize()
     np.testing.assert_allclose(out3.cpu().numpy().astype(np.float64),
                                oracle.aggregate_scores(s32[::2], None, reduce_heads), rtol=2e-6, atol=1e-12)
+
+
+# ------------------------------------ the refinement stages chained end to end
+def test_refinement_pipeline_end_to_end():
+    """Attention + importance -> sum over heads -> sentence-level selection under the token
+    budget floor(r * l) with a protected prefix and suffix -> bit stream.  Importance parity is
+    covered above; here every later stage is checked against the oracle applied to the scores
+    the previous GPU stage produced."""
+    wl = W.make_custom("t", [1500, 333], None, 8, 2, 128, 48, "1/4", seed=9)
+    dev = DeviceWorkload(wl)
+    dev.step()
+    imp = dev.imp                                               # [Hkv, total_k] fp32 on the GPU
+    oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, wl.window)
+    rel_close(imp.cpu().numpy().astype(np.float64), oI, "importance")
+    # all heads into one score row
+    allh = torch.empty((1, wl.total_k), dtype=torch.float32, device="cuda")
+    pdd.aggregate_scores(imp.view(1, wl.n_kv_heads, wl.total_k), allh, None, reduce_heads=True)
+    torch.cuda.synchronize()
+    want_all = oracle.aggregate_scores(imp.cpu().numpy()[None], None, True)
+    np.testing.assert_allclose(allh.cpu().numpy().astype(np.float64), want_all, rtol=2e-6, atol=1e-12)
+    # sentences over the content part, prefix of 20 and suffix of 12 tokens protected
+    rng = np.random.default_rng(4)
+    lens = np.diff(wl.cu_seqlens_k)
+    cb = np.array([20, 20], dtype=np.int32)
+    ends, cu_sent = [], [0]
+    for b in range(2):
+        ends += _sentence_split(rng, 20, int(lens[b]) - 12, 15, False)
+        cu_sent.append(len(ends))
+    ends = np.array(ends, dtype=np.int32)
+    cu_sent = np.array(cu_sent, dtype=np.int32)
+    budget = np.array([int(lens[b]) // 4 for b in range(2)], dtype=np.int32)   # floor(r * l), r = 1/4
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    sscore = torch.empty((1, len(ends)), dtype=torch.float32, device="cuda")
+    skeep = torch.empty((1, len(ends)), dtype=torch.uint8, device="cuda")
+    mask = torch.full((1, wl.total_k), 9, dtype=torch.uint8, device="cuda")
+    kept = torch.empty((1, 2), dtype=torch.int32, device="cuda")
+    pdd.select_sentences(allh, dev.cu_k, dev.max_k, d(cu_sent), d(ends), int(np.diff(cu_sent).max()),
+                         d(budget), pdd.SENT_MEAN, d(cb), sscore, skeep, mask, kept, wl.cu_seqlens_k)
+    torch.cuda.synchronize()
+    w_sc, w_keep, w_mask, w_kept = oracle.select_sentences(
+        allh.cpu().numpy().astype(np.float64), wl.cu_seqlens_k, cu_sent, ends, budget, "mean", cb)
+    np.testing.assert_allclose(sscore.cpu().numpy().astype(np.float64), w_sc, rtol=2e-6, atol=1e-12)
+    # the decision, on the sentence scores the kernel ranked
+    g_sc = sscore.cpu().numpy().astype(np.float64)
+    for b in range(2):
+        sl = slice(cu_sent[b], cu_sent[b + 1])
+        e = ends[sl]
+        ln = np.diff(np.concatenate([[cb[b]], e]))
+        order = np.lexsort((np.arange(len(e)), -g_sc[0, sl]))
+        fit = np.cumsum(ln[order]) <= budget[b]
+        m = int(fit.sum()) if fit.all() else int(np.argmin(fit))
+        want = np.zeros(len(e), dtype=np.uint8)
+        want[order[:m]] = 1
+        assert np.array_equal(skeep.cpu().numpy()[0, sl], want)
+        assert int(kept.cpu().numpy()[0, b]) == int(ln[want == 1].sum()) <= budget[b]
+        seq = mask.cpu().numpy()[0, wl.cu_seqlens_k[b]:wl.cu_seqlens_k[b + 1]]
+        assert seq[:20].sum() == 0 and seq[int(lens[b]) - 12:].sum() == 0 and seq.sum() == int(ln[want == 1].sum())
+    # bit stream of the token mask
+    want_bits, cu_bytes = oracle.pack_mask(mask.cpu().numpy(), wl.cu_seqlens_k)
+    bits = torch.empty((1, int(cu_bytes[-1])), dtype=torch.uint8, device="cuda")
+    pdd.pack_mask(mask, dev.cu_k, dev.max_k, d(cu_bytes), int(cu_bytes[-1]), bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits.cpu().numpy(), want_bits)
