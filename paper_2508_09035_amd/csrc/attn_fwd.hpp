@@ -57,10 +57,12 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 __device__ __forceinline__ float max3(float a, float b, float c)
 {
-    // v_max3_f32; inputs are never NaN here, so no canonicalisation is needed
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
+    // Compiles to one v_max3_f32.  Deliberately not inline assembly: the operands are MFMA
+    // results, and only for instructions it knows does the compiler insert the wait states
+    // the hardware needs between an MFMA writing a register and a VALU instruction reading it
+    // (an assembly v_max3 right behind the MFMA reads the accumulator before the last pass
+    // has written it, which made the running max, and with it the rounding, depend on timing).
+    return fmaxf(fmaxf(a, b), c);
 }
 
 __device__ __forceinline__ float xchg_half(float x)

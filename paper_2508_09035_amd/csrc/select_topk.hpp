@@ -40,6 +40,7 @@ struct SelParams {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelFinish = 64;    // keys left in the bracket that are ranked directly
 constexpr int kSelRegCap = 32 * 1024;  // rows up to this many candidates stay in registers
 
 // Score of key j after 1-D pooling along the sequence (paper Section 3.2: "applying 1D
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
     __shared__ uint32_t wave_min[kSelWaves], wave_max[kSelWaves];
     __shared__ uint32_t cnt[kSelWaves * EPT];          // per (i, wave): gt count | eq count << 16
     __shared__ uint32_t cnt_wave_tot[kSelWaves];
+    __shared__ uint32_t fin_keys[kSelFinish], fin_count, fin_T, fin_above;
 
     const int b = blockIdx.x, g = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -116,11 +118,26 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
     // ---- keys into registers; row range
     uint32_t key[EPT];
     uint32_t kmin = 0xffffffffu, kmax = 0u;
+    if (p.pool_r == 0) {
+        // no pooling: plain loads, all of them in flight before the first one is used
+        float raw[EPT];
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int x = i * kSelThreads + tid;
+            raw[i] = x < n ? seq[c0 + x] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) key[i] = (i * kSelThreads + tid < n) ? order_key(raw[i]) : 0u;
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int x = i * kSelThreads + tid;
+            key[i] = x < n ? order_key(pooled_score(seq, nk, c0 + x, p.pool_r, p.pool_mode, p.pool_inv)) : 0u;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < EPT; ++i) {
-        const int x = i * kSelThreads + tid;
-        const bool in = x < n;
-        key[i] = in ? order_key(pooled_score(seq, nk, c0 + x, p.pool_r, p.pool_mode, p.pool_inv)) : 0u;
+        const bool in = i * kSelThreads + tid < n;
         kmin = in ? min(kmin, key[i]) : kmin;
         kmax = in ? max(kmax, key[i]) : kmax;
     }
@@ -134,12 +151,18 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
 
-    // ---- bisection: largest T in [kmin, kmax] with count(key >= T) >= kk.
+    // ---- threshold search: largest T in [kmin, kmax] with count(key >= T) >= kk.
+    // Bisection on the key value with the bracket [lo, hi] and the two counts
+    // c_lo = count(key >= lo) >= kk > c_above = count(key > hi); once at most kSelFinish keys
+    // are left inside the bracket they are collected in LDS and ranked directly (about 12
+    // probes instead of 27 for a row of 32768; probing the point where a straight line through
+    // the two counts crosses kk was tried and needs more probes: it converges from one side).
     // Invalid slots hold key 0 and every probed T is > kmin >= 0, so they never count.
     uint32_t lo = kmin, hi = kmax;
+    uint32_t c_lo = (uint32_t)n;       // count(key >= lo)
     uint32_t c_above = 0;              // count(key >= hi + 1) = count(key > T) at the end
     int par = 0;
-    while (lo < hi) {
+    while (lo < hi && c_lo - c_above > (uint32_t)kSelFinish) {
         const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
         uint32_t c = 0;
 #pragma unroll
@@ -150,8 +173,39 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
 #pragma unroll
         for (int w = 0; w < kSelWaves; ++w) tot += wred[par][w];
         par ^= 1;
-        if (tot >= (uint32_t)kk) lo = mid;
+        if (tot >= (uint32_t)kk) { lo = mid; c_lo = tot; }
         else { hi = mid - 1u; c_above = tot; }
+    }
+    if (lo < hi) {
+        // at most kSelFinish keys lie in [lo, hi]: the (kk - c_above)-th largest of them is T
+        if (tid == 0) fin_count = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const bool in = i * kSelThreads + tid < n;
+            if (in && key[i] >= lo && key[i] <= hi) {
+                const uint32_t slot = atomicAdd(&fin_count, 1u);
+                if (slot < (uint32_t)kSelFinish) fin_keys[slot] = key[i];
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const uint32_t m = min(fin_count, (uint32_t)kSelFinish);
+            const uint32_t mine_k = lane < (int)m ? fin_keys[lane] : 0u;
+            uint32_t gt = 0, ge = 0;
+            for (uint32_t j = 0; j < m; ++j) {
+                const uint32_t o = fin_keys[j];
+                gt += o > mine_k ? 1u : 0u;
+                ge += o >= mine_k ? 1u : 0u;
+            }
+            const uint32_t r = (uint32_t)kk - c_above;                    // 1 <= r <= m
+            const bool hit = lane < (int)m && gt < r && r <= ge;          // every hit lane holds the same key
+            const uint64_t hb = __ballot(hit);
+            if (hb != 0 && lane == (int)__builtin_ctzll(hb)) { fin_T = mine_k; fin_above = c_above + gt; }
+        }
+        __syncthreads();
+        lo = fin_T;
+        c_above = fin_above;
     }
     const uint32_t T = lo;
     const int krem = kk - (int)c_above;     // ties at T to keep (>= 1), lowest index first

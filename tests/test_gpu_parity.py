@@ -133,6 +133,25 @@ def test_standalone_importance_equals_fused_and_is_deterministic():
     assert (dev.imp == -5.0).all()
 
 
+@pytest.mark.parametrize("name", ["c5", "c3"])
+def test_results_are_bit_identical_run_to_run(name):
+    """The whole path twice on the same inputs: identical bits.  Large launches matter here:
+    a read of an MFMA result before its last pass had been written (an assembly instruction
+    the compiler could not guard) once made the running max, and so the rounding of O and lse,
+    depend on how the two waves of a SIMD interleaved."""
+    wl = W.make_workload(name)
+    dev = DeviceWorkload(wl)
+    dev.step()
+    torch.cuda.synchronize()
+    ref = [x.copy() for x in dev.results()]
+    for _ in range(3):
+        dev.poison()
+        dev.step()
+        torch.cuda.synchronize()
+        for what, a, b in zip(("O", "lse", "importance", "indices", "mask"), ref, dev.results()):
+            assert np.array_equal(a, b), f"{name}: {what} differs between two runs"
+
+
 # ------------------------------------------------------------- selection alone
 def _select_case(scores64, lens, ks, cand=None, rel_tie=1e-6):
     """Gate A: the oracle's scores rounded to fp32 go through the GPU select."""
