@@ -49,13 +49,14 @@ __device__ __forceinline__ i32x4 make_rsrc(const void *base, uint32_t bytes)
 // (lds_addr wave-uniform).  Out-of-range lanes write zeros.  Written as inline
 // assembly so that the transfer stays asynchronous: completion is awaited with
 // an explicit s_waitcnt vmcnt(0) before the workgroup barrier that publishes
-// the tile.  Nothing else in this kernel relies on M0.
+// the tile.  M0 is declared clobbered, so the compiler neither keeps a value in it across
+// the transfer nor misses the wait state after the write.
 __device__ __forceinline__ void dma16_to_lds(i32x4 rsrc, uint32_t lds_addr, uint32_t voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ uint32_t lds_addr_of(const void *p)

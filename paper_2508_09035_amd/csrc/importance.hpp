@@ -46,7 +46,7 @@ __device__ __forceinline__ void dma4_to_lds(i32x4 rsrc, uint32_t lds_addr, uint3
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 template <int N>
