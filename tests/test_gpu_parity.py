@@ -133,7 +133,7 @@ def test_standalone_importance_equals_fused_and_is_deterministic():
     assert (dev.imp == -5.0).all()
 
 
-@pytest.mark.parametrize("name", ["c5", "c3"])
+@pytest.mark.parametrize("name", ["c5", "c3", "c4"])
 def test_results_are_bit_identical_run_to_run(name):
     """The whole path twice on the same inputs: identical bits.  Large launches matter here:
     a read of an MFMA result before its last pass had been written (an assembly instruction
@@ -144,7 +144,7 @@ def test_results_are_bit_identical_run_to_run(name):
     dev.step()
     torch.cuda.synchronize()
     ref = [x.copy() for x in dev.results()]
-    for _ in range(3):
+    for _ in range(1 if name == "c4" else 3):
         dev.poison()
         dev.step()
         torch.cuda.synchronize()
