@@ -288,6 +288,15 @@ pdd_status pdd_choose_r_L(const pdd_rl_model *model, int32_t l, double *r, int32
  *             a sequence longer than 8 * its byte count is truncated
  *   out_bits  DEVICE uint8 [n_rows, total_bytes]                          -- out
  */
+/*
+ * Layout and size of that bit stream (host only, no GPU work): fills
+ * cu_bytes_host[0..B] with the prefix sums of ceil(Nk_b / 8) and returns their
+ * total, the number of bytes per row before compression (Section 3.2 sends the
+ * compressed stream along with the first token; Section 5 discusses its size).
+ * Returns -1 on a NULL pointer, batch < 1 or a decreasing cu_seqlens_k_host.
+ */
+int64_t pdd_pack_mask_layout(int32_t batch, const int32_t *cu_seqlens_k_host, int32_t *cu_bytes_host);
+
 pdd_status pdd_pack_mask(const uint8_t *mask, int32_t n_rows, int32_t batch, int32_t total_k,
                          const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host,
                          int32_t max_seqlen_k, const int32_t *cu_bytes, int32_t total_bytes,

@@ -23,6 +23,7 @@ from .binding import (
     SENT_SUM,
     SENT_MEAN,
     pack_mask,
+    pack_mask_layout,
     aggregate_scores,
     choose_r_L,
     workspace_bytes,
@@ -33,6 +34,6 @@ from .binding import (
 
 __all__ = [
     "PddError", "library_path", "load_library", "version", "set_option", "prefill_attn",
-    "prefill_attn_chunked", "token_importance", "select_topk", "select_topk_pooled", "POOL_NONE", "POOL_MAX", "POOL_AVG", "select_sentences", "SENT_SUM", "SENT_MEAN", "pack_mask", "aggregate_scores", "choose_r_L", "workspace_bytes", "AttnDesc",
+    "prefill_attn_chunked", "token_importance", "select_topk", "select_topk_pooled", "POOL_NONE", "POOL_MAX", "POOL_AVG", "select_sentences", "SENT_SUM", "SENT_MEAN", "pack_mask", "pack_mask_layout", "aggregate_scores", "choose_r_L", "workspace_bytes", "AttnDesc",
     "make_desc", "OPT_ATTN_WAVES",
 ]

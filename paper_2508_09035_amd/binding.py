@@ -79,6 +79,8 @@ def load_library():
     lib.pdd_choose_r_L.restype = ctypes.c_int
     lib.pdd_choose_r_L.argtypes = [ctypes.POINTER(RLModel), i32, ctypes.POINTER(ctypes.c_double),
                                    ctypes.POINTER(ctypes.c_int32)]
+    lib.pdd_pack_mask_layout.restype = ctypes.c_int64
+    lib.pdd_pack_mask_layout.argtypes = [i32, vp, vp]
     lib.pdd_pack_mask.restype = ctypes.c_int
     lib.pdd_pack_mask.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, i32, vp, vp]
     lib.pdd_workspace_bytes.restype = sz
@@ -272,6 +274,18 @@ def choose_r_L(l, k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau):
     r, L = ctypes.c_double(), ctypes.c_int32()
     _check(load_library().pdd_choose_r_L(ctypes.byref(m), int(l), ctypes.byref(r), ctypes.byref(L)))
     return r.value, L.value
+
+
+def pack_mask_layout(cu_seqlens_k_host):
+    """pdd_pack_mask_layout (host only): int32 numpy prefix sums of the per-sequence byte
+    counts of the bit stream, and the bytes per row."""
+    import numpy as np
+    cu = np.ascontiguousarray(cu_seqlens_k_host, dtype=np.int32)
+    out = np.zeros(len(cu), dtype=np.int32)
+    total = load_library().pdd_pack_mask_layout(len(cu) - 1, cu.ctypes.data, out.ctypes.data)
+    if total < 0:
+        raise PddError(-1, load_library().pdd_last_error().decode())
+    return out, int(total)
 
 
 def pack_mask(mask, cu_seqlens_k, max_seqlen_k, cu_bytes, total_bytes, out_bits,

@@ -422,6 +422,30 @@ pdd_status pdd_choose_r_L(const pdd_rl_model *m, int32_t l, double *r_out, int32
     return PDD_OK;
 }
 
+int64_t pdd_pack_mask_layout(int32_t batch, const int32_t *cu_seqlens_k_host, int32_t *cu_bytes_host)
+{
+    if (batch < 1 || !cu_seqlens_k_host || !cu_bytes_host) {
+        fail(PDD_ERR_INVALID_ARG, "pdd_pack_mask_layout: bad arguments");
+        return -1;
+    }
+    int64_t total = 0;
+    cu_bytes_host[0] = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int64_t nk = (int64_t)cu_seqlens_k_host[b + 1] - cu_seqlens_k_host[b];
+        if (nk < 0) {
+            fail(PDD_ERR_INVALID_ARG, "pdd_pack_mask_layout: cu_seqlens_k_host decreases at %d", b);
+            return -1;
+        }
+        total += (nk + 7) / 8;
+        if (total > 0x7fffffffLL) {
+            fail(PDD_ERR_INVALID_ARG, "pdd_pack_mask_layout: more than 2^31 bytes per row");
+            return -1;
+        }
+        cu_bytes_host[b + 1] = (int32_t)total;
+    }
+    return total;
+}
+
 pdd_status pdd_pack_mask(const uint8_t *mask, int32_t n_rows, int32_t batch, int32_t total_k,
                          const int32_t *cu_seqlens_k, const int32_t *cu_seqlens_k_host, int32_t max_seqlen_k,
                          const int32_t *cu_bytes, int32_t total_bytes, uint8_t *out_bits, pdd_stream stream)

@@ -188,3 +188,13 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=120)
     assert r.returncode == 2
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_pack_mask_layout_matches_the_oracle_layout():
+    import oracle
+    cu = np.array([0, 13, 77, 77, 1077, 1084, 5183], dtype=np.int32)
+    got, total = pdd.pack_mask_layout(cu)
+    _, want = oracle.pack_mask(np.zeros((1, int(cu[-1])), dtype=np.uint8), cu)
+    assert np.array_equal(got, want) and total == int(want[-1]) == sum((int(n) + 7) // 8 for n in np.diff(cu))
+    with pytest.raises(pdd.PddError):
+        pdd.pack_mask_layout(np.array([0, 5, 3], dtype=np.int32))
