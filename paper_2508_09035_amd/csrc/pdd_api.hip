@@ -156,6 +156,15 @@ pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, con
     return nw == 8 ? launch_attn_t<64, 8>(p, blocks, st) : launch_attn_t<64, 4>(p, blocks, st);
 }
 
+template <int EPT>
+void launch_select_reg(const pdd::SelParams &p, dim3 grid, hipStream_t st)
+{
+    if (p.pool_r == 0)
+        hipLaunchKernelGGL((pdd::select_topk_reg_kernel<EPT, false>), grid, dim3(pdd::kSelThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL((pdd::select_topk_reg_kernel<EPT, true>), grid, dim3(pdd::kSelThreads), 0, st, p);
+}
+
 pdd_status launch_importance(const pdd_attn_desc *d, const void *q, const void *k, const float *lse, float *imp,
                              int window, hipStream_t st)
 {
@@ -305,13 +314,13 @@ pdd_status pdd_select_topk_pooled(const float *scores, int32_t n_heads, int32_t 
     const dim3 grid((unsigned)batch, (unsigned)n_heads);
     hipStream_t st = (hipStream_t)stream;
     if (max_seqlen_k <= 4 * pdd::kSelThreads)
-        hipLaunchKernelGGL(pdd::select_topk_reg_kernel<4>, grid, dim3(pdd::kSelThreads), 0, st, p);
+        launch_select_reg<4>(p, grid, st);
     else if (max_seqlen_k <= 8 * pdd::kSelThreads)
-        hipLaunchKernelGGL(pdd::select_topk_reg_kernel<8>, grid, dim3(pdd::kSelThreads), 0, st, p);
+        launch_select_reg<8>(p, grid, st);
     else if (max_seqlen_k <= 16 * pdd::kSelThreads)
-        hipLaunchKernelGGL(pdd::select_topk_reg_kernel<16>, grid, dim3(pdd::kSelThreads), 0, st, p);
+        launch_select_reg<16>(p, grid, st);
     else if (max_seqlen_k <= 32 * pdd::kSelThreads)
-        hipLaunchKernelGGL(pdd::select_topk_reg_kernel<32>, grid, dim3(pdd::kSelThreads), 0, st, p);
+        launch_select_reg<32>(p, grid, st);
     else
         hipLaunchKernelGGL(pdd::select_topk_kernel, grid, dim3(pdd::kSelThreads), 0, st, p);
     const hipError_t e = hipGetLastError();

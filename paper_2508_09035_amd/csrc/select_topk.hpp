@@ -72,7 +72,8 @@ __device__ __forceinline__ uint32_t order_key(float x)
 // Register-resident selection for rows of at most 1024 * EPT candidates.
 // Thread `tid` owns candidates x = i * 1024 + tid, i = 0 .. EPT-1.
 // ---------------------------------------------------------------------------
-template <int EPT>
+// POOL = false: the instantiation for unpooled scores carries none of the pooling code.
+template <int EPT, bool POOL>
 __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelParams p)
 {
     __shared__ uint32_t wred[2][kSelWaves];            // per-wave partial counts (double buffered)
@@ -102,7 +103,11 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
 
     if (p.pooled_out) {
         float *po = p.pooled_out + (int64_t)g * p.total_k + ks;
-        for (int x = tid; x < nk; x += kSelThreads) po[x] = pooled_score(seq, nk, x, p.pool_r, p.pool_mode, p.pool_inv);
+        if constexpr (POOL) {
+            for (int x = tid; x < nk; x += kSelThreads) po[x] = pooled_score(seq, nk, x, p.pool_r, p.pool_mode, p.pool_inv);
+        } else {
+            for (int x = tid; x < nk; x += kSelThreads) po[x] = seq[x];
+        }
     }
     if (mrow) {
         for (int x = tid; x < c0; x += kSelThreads) mrow[x] = 0;
@@ -118,14 +123,12 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
     // ---- keys into registers; row range
     uint32_t key[EPT];
     uint32_t kmin = 0xffffffffu, kmax = 0u;
-    if (p.pool_r == 0) {
-        // no pooling: plain loads, all of them in flight before the first one is used
+    if constexpr (!POOL) {
+        // plain loads from clamped (always valid: n >= 1 here) addresses, so that all of them are
+        // in flight before the first one is used
         float raw[EPT];
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-            const int x = i * kSelThreads + tid;
-            raw[i] = x < n ? seq[c0 + x] : 0.f;
-        }
+        for (int i = 0; i < EPT; ++i) raw[i] = seq[c0 + min(i * kSelThreads + tid, n - 1)];
 #pragma unroll
         for (int i = 0; i < EPT; ++i) key[i] = (i * kSelThreads + tid < n) ? order_key(raw[i]) : 0u;
     } else {
