@@ -83,6 +83,30 @@ def test_chunked_small(waves):
     run_and_compare(wl, waves=waves, label=f"chunked w={waves}")
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes(seed):
+    """Seeded random small problems: batch, lengths around the 64-key tile and 256-row
+    workgroup boundaries, head grouping, head_dim, window, plain or chunked."""
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.integers(1, 5))
+    edges = np.array([1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 255, 256, 257, 320, 511, 512, 513, 700])
+    lens_q = [int(rng.choice(edges)) if rng.random() < 0.6 else int(rng.integers(1, 700)) for _ in range(B)]
+    hq, hkv = [(1, 1), (4, 1), (4, 2), (8, 8), (6, 2), (8, 2)][int(rng.integers(0, 6))]
+    d = int(rng.choice([64, 128]))
+    chunked = bool(rng.random() < 0.4)
+    if chunked:
+        lens_k = [q + (int(rng.choice(edges)) if rng.random() < 0.7 else 0) for q in lens_q]
+        wl = W.make_custom("t", lens_q, lens_k, hq, hkv, d, 0, "1/3", seed=seed, chunked=True)
+        for b in range(B):                              # a chunk without a prefix has no candidates
+            if lens_k[b] == lens_q[b]:
+                wl.cand_end[b] = 0
+                wl.k_keep[b] = 0
+    else:
+        wl = W.make_custom("t", lens_q, None, hq, hkv, d, int(rng.integers(1, 100)), "1/3", seed=seed)
+    run_and_compare(wl, waves=int(rng.choice([0, 4, 8])),
+                    label=f"random {seed}: q={lens_q} chunked={chunked} heads={hq}/{hkv} d={d}")
+
+
 def test_empty_sequence_in_batch_and_no_host_copies():
     wl = W.make_custom("t", [40, 0, 129], None, 2, 1, 64, 16, "1/2", seed=9)
     dev = DeviceWorkload(wl)
