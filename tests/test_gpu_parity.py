@@ -243,6 +243,15 @@ def _sample_rows(wl, per_seq_random, tile=256, seed=0):
     return np.array(rows, dtype=np.int32)
 
 
+@pytest.mark.parametrize("waves", [4, 8])
+def test_head_dim_64_longer_prompts_sampled_rows(waves):
+    """The head_dim-64 kernel on prompts of many tiles (the graded configurations with d = 64
+    stop at 512 tokens)."""
+    wl = W.make_custom("t", [3000, 1111], None, 8, 2, 64, 64, "1/4", seed=77)
+    o_err, swapped = run_and_compare(wl, rows=_sample_rows(wl, 48), waves=waves, label=f"d64 long w={waves}")
+    assert swapped == 0
+
+
 def test_c3_ragged_batch_sampled_rows():
     wl = W.make_workload("c3")
     rows = _sample_rows(wl, 48)
