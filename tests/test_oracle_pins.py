@@ -459,3 +459,34 @@ def test_choose_r_L_search_matches_closed_form():
     assert oracle.choose_r_L(8192, 0.4, 0.5, 300, 0.6, 30, 50, 100) is None
     # Eq. 6 empty: the smoothing needs more cloud tokens than the occupation bound allows
     assert oracle.choose_r_L(8192, 0.02, 0.5, 300, 0.6, 300, 50, 60) is None
+
+
+# --------------------------------------- hand-worked fixture of the refinement stages
+def test_refinement_stages_against_the_hand_worked_fixture():
+    """tests/golden/refinement_handworked.json: sentence-level selection, pooling, bit stream
+    and layer aggregation worked by hand from the definitions."""
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "refinement_handworked.json")) as f:
+        fx = json.load(f)
+    s = fx["sentences"]
+    sc = np.array([s["scores"]], dtype=np.float64)
+    n, ends, cb = len(s["scores"]), s["sentence_ends"], [s["content_begin"]]
+    run = lambda mode, budget: oracle.select_sentences(sc, [0, n], [0, len(ends)], ends, [budget], mode, cb)
+    assert run("sum", 5)[0].tolist() == [s["sums"]] and run("mean", 5)[0].tolist() == [s["means"]]
+    assert run("sum", 5)[1].tolist() == [s["sum_budget5_keep"]] and run("sum", 5)[2].tolist() == [s["sum_budget5_mask"]]
+    assert run("sum", 4)[1].tolist() == [s["sum_budget4_keep"]]
+    assert run("sum", 3)[1].tolist() == [s["sum_budget3_keep"]]
+    assert run("mean", 5)[1].tolist() == [s["mean_budget5_keep"]]
+    assert run("mean", 2)[1].tolist() == [s["mean_budget2_keep"]] and run("mean", 2)[2].tolist() == [s["mean_budget2_mask"]]
+    p = fx["pooling"]
+    ps = np.array([p["scores"]], dtype=np.float64)
+    assert oracle.pool_scores(ps, p["cu_seqlens"], 3, "max").tolist() == [p["max_k3"]]
+    np.testing.assert_allclose(3 * oracle.pool_scores(ps, p["cu_seqlens"], 3, "avg"), [p["avg_k3_times3"]], rtol=1e-15)
+    b = fx["bit_stream"]
+    bits, _ = oracle.pack_mask(np.array([b["mask"]], dtype=np.uint8), b["cu_seqlens"])
+    assert bits.tolist() == [b["bytes"]]
+    a = fx["aggregation"]
+    stack = np.arange(24, dtype=np.float64).reshape(2, 3, 4)
+    assert oracle.aggregate_scores(stack, a["weights"]).tolist() == a["per_head"]
+    assert oracle.aggregate_scores(stack, a["weights"], reduce_heads=True).tolist() == a["heads_reduced"]
