@@ -178,8 +178,8 @@ pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch,
 
 /*
  * Selection with 1-D pooling of the scores first (Section 3.2 "Prompt Refiner":
- * after summing the weight along the query dimension, 1-D pooling "for
- * clustering", then sorting).  The paper gives neither kernel size nor type;
+ * after summing the weight along the query dimension, a 1-D pooling step that
+ * lets neighbouring tokens be kept together, then sorting).  The paper gives neither kernel size nor type;
  * both are parameters here.  Pooled score of key j = reduction over keys
  * [j - r, j + r] of the same sequence, r = (pool_kernel - 1) / 2, stride 1:
  *   PDD_POOL_MAX  maximum over the part of the window inside the sequence

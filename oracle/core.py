@@ -163,7 +163,7 @@ def pack_mask(mask: np.ndarray, cu_k):
 
 def pool_scores(scores: np.ndarray, cu_k, kernel: int, mode: str) -> np.ndarray:
     """1-D pooling of the summed scores along each sequence before sorting
-    (Section 3.2 "Prompt Refiner": "applying 1D pooling for clustering").
+    (Section 3.2 "Prompt Refiner": a pooling step that clusters neighbouring tokens).
     Window of key j: keys [j - r, j + r] of the same sequence, r = (kernel-1)/2.
     mode "max": maximum over the part of the window inside the sequence;
     mode "avg": sum over that part divided by `kernel` (zero padding).

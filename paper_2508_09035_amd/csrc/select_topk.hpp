@@ -43,8 +43,8 @@ constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelFinish = 64;    // keys left in the bracket that are ranked directly
 constexpr int kSelRegCap = 32 * 1024;  // rows up to this many candidates stay in registers
 
-// Score of key j after 1-D pooling along the sequence (paper Section 3.2: "applying 1D
-// pooling for clustering" between the sum over queries and the sort).  Window = keys
+// Score of key j after 1-D pooling along the sequence (paper Section 3.2: a pooling step
+// between the sum over queries and the sort, so that neighbours are kept together).  Window = keys
 // [j-r, j+r] inside the sequence; max over the valid part, or sum of the valid part divided by
 // the kernel size (zero padding).  seq = first score of the sequence row, nk = its length.
 __device__ __forceinline__ float pooled_score(const float *seq, int nk, int j, int r, int mode, float inv)
