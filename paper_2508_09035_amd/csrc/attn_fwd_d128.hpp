@@ -294,6 +294,11 @@ void attn_fwd_d128_kernel(const AttnParams p)
     };
     // The wave runs at raised issue priority while it has the exponentials to do and at normal
     // priority during its PV MFMAs (measured: 1 % on the 32k prompt, 3 % on constant inputs).
+    auto premul = [&](f32x16 &s, float m) {
+        const float nm = -m * c2;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[e] = fmaf(s[e], c2, nm);
+    };
     auto hot_half = [&](f32x16 &cur, f32x16 &nxt, float &m_cand, uint32_t k_next2, uint32_t v_cur) {
         __builtin_amdgcn_s_setprio(1);
         if (__any(m_cand > m_run)) rescale(m_cand);
@@ -306,7 +311,8 @@ void attn_fwd_d128_kernel(const AttnParams p)
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk)
             nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], kk == 0 ? zero16 : nxt, 0, 0, 0);
-        exp_block(cur);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cur[e] = fast_exp2(cur[e]);   // cur holds s * c2 - m * c2 (see below)
         __builtin_amdgcn_s_setprio(0);
         load_kf(k_next2);
 #pragma unroll
@@ -319,7 +325,13 @@ void attn_fwd_d128_kernel(const AttnParams p)
             for (int db = 0; db < NDB; ++db)
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pb, oacc[db], 0, 0, 0);
         }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) l_part[e & 3] += cur[e];      // row sums: also in this phase
         m_cand = row_max(nxt);
+        // The scale-and-subtract of the next block is done here, in the phase whose VALU is
+        // otherwise idle, against the max the next phase 1 will adopt (m_cand >= m_run, and the
+        // rescale at the start of that phase sets m_run = m_cand in the lanes where it moved).
+        premul(nxt, m_cand);
     };
     auto hot_tile = [&](auto par_c, const int it, float &m_cand) {
         constexpr int PAR = decltype(par_c)::value;
@@ -334,6 +346,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
     int it = 0;
     if (n_hot > 0) {
         float m_cand = row_max(sA);
+        premul(sA, m_cand);
         load_kf(32 * 256);
         for (; it + 3 <= n_hot; it += 3) {          // unrolled over the three LDS buffers
             hot_tile(std::integral_constant<int, 0>{}, it, m_cand);
@@ -342,6 +355,9 @@ void attn_fwd_d128_kernel(const AttnParams p)
         }
         if (it < n_hot) { hot_tile(std::integral_constant<int, 0>{}, it, m_cand); ++it; }
         if (it < n_hot) { hot_tile(std::integral_constant<int, 1>{}, it, m_cand); ++it; }
+        // the hot loop leaves sA scaled and shifted; the generic loop wants the raw scores of its
+        // first block (one extra QK block per workgroup)
+        qk_block((uint32_t)(it % 3) * kTileBytes, sA);
     }
 
     // ---- remaining tiles (the diagonal region): per-wave activity and masking
