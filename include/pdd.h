@@ -164,8 +164,11 @@ pdd_status pdd_token_importance(const pdd_attn_desc *desc, const void *q, const 
  *   out_indices  DEVICE int32 [n_heads, total_keep]: sequence-local key
  *                indices in ascending order                              -- out
  *   out_mask     DEVICE uint8 [n_heads, total_k] or NULL: 1 = selected   -- out
- * A k_b larger than the candidate count is clamped on the device (the host
- * cannot see it); the surplus index slots are filled with -1.
+ * A k_b larger than the candidate count is not an argument error here: k_per_seq
+ * and the candidate ranges live in device memory, which the library never reads
+ * from the host, so the count is clamped on the device and the surplus index
+ * slots are filled with -1 (callers that want the error check k_b on their side,
+ * where they computed it).
  * -0.0 ranks equal to +0.0.
  */
 pdd_status pdd_select_topk(const float *scores, int32_t n_heads, int32_t batch,
@@ -256,16 +259,20 @@ pdd_status pdd_aggregate_scores(const float *scores, int32_t n_layers, int32_t n
                                 int32_t accumulate, float *out, pdd_stream stream);
 
 /*
- * Refinement ratio r and early-termination length L (Section 3.5, program P:
- * minimise the on-device TTFT subject to Eq. 5 on r and Eq. 6 on L; Section
- * 4.2 observes that the optimum sits at L's lower bound).  Host-only scalar
- * code, no GPU work.  With TTFT_c = k_c*l, prefill_d(x) = k_d*x and
- * TTFT_d = k_c*l + delta + k_d*r*l the objective grows with r, so
- *   r = xi_scene                     (must be <= 1 - (k_c + delta/l)/k_d, Eq. 5)
- *   L = 1 + max(1, ceil((k_d*r*l - k_c*l) / (tau - tpot_d)))
- *                                    (must satisfy L-1 <= (TTFT_d - TTFT_c)/tpot_c, Eq. 6)
- * Returns PDD_ERR_INFEASIBLE when either range is empty; *r and *L are then
- * left untouched.  Times in one unit throughout (k_* per token).
+ * Refinement ratio r and early-termination length L (Section 3.4 "Algorithm
+ * on Refiner and Termination", program P: minimise the on-device TTFT subject
+ * to Eq. 5 on r and Eq. 6 on L; Section 4.2 observes that the optimum sits at
+ * L's lower bound).  Host-only scalar code, no GPU work.  With
+ *   TTFT_c = k_c*l + delta_cloud                  (Eq. 2: prefill + compress + RTT)
+ *   TTFT_d = TTFT_c + (delta - delta_cloud) + k_d*r*l
+ *          = k_c*l + delta + k_d*r*l              (Eq. 3: + decompress + device prefill)
+ * the objective grows with r, so the answer is the smallest admissible ratio:
+ *   L - 1 = n = max(1, ceil((k_d*xi_scene*l - TTFT_c) / (tau - tpot_d)))   (Eq. 6, lower bound)
+ *   r     = max(xi_scene, (n*tpot_c - (delta - delta_cloud)) / (k_d*l))    (Eq. 6, upper bound:
+ *           a larger r lengthens the device prefill until the cloud's n tokens fit inside it)
+ * provided r <= 1 - (k_c + delta/l)/k_d (Eq. 5) and k_d*r*l <= n*(tau - tpot_d) + TTFT_c.
+ * Returns PDD_ERR_INFEASIBLE when no pair satisfies both constraints; *r and
+ * *L are then left untouched.  Times in one unit throughout (k_* per token).
  */
 typedef struct pdd_rl_model {
     double k_c, k_d;       /* prefill time per prompt token: cloud, device      */
@@ -273,6 +280,9 @@ typedef struct pdd_rl_model {
     double xi_scene;       /* smallest ratio the scenario's quality allows      */
     double tpot_c, tpot_d; /* time per output token: cloud, device              */
     double tau;            /* largest tolerable smoothed TPOT                   */
+    double delta_cloud;    /* the part of delta that passes before the first
+                              token reaches the device (compress + RTT);
+                              0 <= delta_cloud <= delta                         */
 } pdd_rl_model;
 pdd_status pdd_choose_r_L(const pdd_rl_model *model, int32_t l, double *r, int32_t *L);
 
@@ -283,16 +293,18 @@ pdd_status pdd_choose_r_L(const pdd_rl_model *model, int32_t l, double *r, int32
  * token in the most significant bit, unused tail bits zero.
  *
  *   mask      DEVICE uint8 [n_rows, total_k], non-zero = selected          -- in
- *   cu_bytes  DEVICE int32[B+1] prefix sums of the per-sequence byte counts,
- *             each at least ceil(Nk_b / 8); spare bytes are written as zero;
- *             a sequence longer than 8 * its byte count is truncated
+ *   cu_bytes  DEVICE int32[B+1] prefix sums of the per-sequence byte counts
+ *             (pdd_pack_mask_layout gives ceil(Nk_b / 8) each); a count larger
+ *             than that leaves the spare bytes untouched, a smaller one
+ *             truncates the sequence
  *   out_bits  DEVICE uint8 [n_rows, total_bytes]                          -- out
  */
 /*
  * Layout and size of that bit stream (host only, no GPU work): fills
  * cu_bytes_host[0..B] with the prefix sums of ceil(Nk_b / 8) and returns their
  * total, the number of bytes per row before compression (Section 3.2 sends the
- * compressed stream along with the first token; Section 5 discusses its size).
+ * compressed stream along with the first token; Section 3.2 "Prompt Refiner" and
+ * Section 4.3 discuss its size).
  * Returns -1 on a NULL pointer, batch < 1 or a decreasing cu_seqlens_k_host.
  */
 int64_t pdd_pack_mask_layout(int32_t batch, const int32_t *cu_seqlens_k_host, int32_t *cu_bytes_host);

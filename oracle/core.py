@@ -247,28 +247,38 @@ def aggregate_scores(scores, weights=None, reduce_heads=False, acc=None):
     return out if acc is None else out + np.asarray(acc, dtype=np.float64)
 
 
-def choose_r_L(l, k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau, r_grid=2000, L_max=5000):
-    """Program P of Section 3.5 by exhaustive search: minimise
-    TTFT_d = k_c l + delta + k_d r l over a grid of ratios r in [0, 1] (the grid
-    contains xi_scene) and integers 2 <= L <= L_max, subject to Eq. 5
-    (xi_scene <= r <= 1 - (k_c + delta/l)/k_d) and Eq. 6
+def choose_r_L(l, k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau, delta_cloud=0.0, r_grid=2000,
+               L_max=5000):
+    """Program P of Section 3.4 ("Algorithm on Refiner and Termination") by exhaustive
+    search in exact rational arithmetic: minimise TTFT_d over candidate ratios r in [0, 1]
+    and integers 2 <= L <= L_max.
+      Eq. 2:  TTFT_c = prefill_c(l) + compress + RTT       = k_c l + delta_cloud
+      Eq. 3:  TTFT_d = TTFT_c + decompress + prefill_d(rl) = k_c l + delta + k_d r l
+    with delta the bound on compress + decompress + RTT and delta_cloud its part spent before
+    the first token reaches the device (compress + RTT), 0 <= delta_cloud <= delta.
+    Subject to Eq. 5 (xi_scene <= r <= 1 - (k_c + delta/l)/k_d) and Eq. 6
     ((prefill_d(rl) - TTFT_c)/(tau - TPOT_d) <= L-1 <= (TTFT_d - TTFT_c)/TPOT_c).
-    Among minimisers the smallest L is returned (Section 4.2: the optimum is at
-    L's lower bound).  Returns (r, L) or None when nothing is feasible."""
+    r is a real number, so besides a uniform grid and xi_scene the candidates include every
+    ratio at which the cloud-occupation bound of Eq. 6 becomes tight for an integer L (the
+    only other places where the feasible set can start).  Among minimisers the smallest L is
+    returned (Section 4.2: the optimum is at L's lower bound).  Returns (r, L) with r a
+    float, or None when nothing is feasible."""
+    from fractions import Fraction as F
+    from math import ceil
+    l, k_c, k_d, delta, xi, tpot_c, tpot_d, tau, d_c = (
+        F(x) for x in (l, k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau, delta_cloud))
+    assert 0 <= d_c <= delta and tau > tpot_d
+    cands = {F(i, r_grid) for i in range(r_grid + 1)} | {xi}
+    cands |= {((L - 1) * tpot_c - (delta - d_c)) / (k_d * l) for L in range(2, L_max + 1)}
     best = None
-    rs = sorted(set([i / r_grid for i in range(r_grid + 1)] + [xi_scene]))
-    for r in rs:
-        if not (xi_scene <= r <= 1 - (k_c + delta / l) / k_d):
+    for r in sorted(c for c in cands if 0 <= c <= 1):
+        if not (xi <= r <= 1 - (k_c + delta / l) / k_d):
             continue
-        ttft_c = k_c * l
-        ttft_d = k_c * l + delta + k_d * r * l
-        for L in range(2, L_max + 1):
-            smooth_ok = (k_d * r * l - ttft_c) <= (L - 1) * (tau - tpot_d)
-            cloud_ok = ttft_c + (L - 1) * tpot_c <= ttft_d
-            if smooth_ok and cloud_ok:
-                if best is None or ttft_d < best[0]:
-                    best = (ttft_d, r, L)
-                break                     # larger L never lowers TTFT_d for this r
-            if not cloud_ok:
-                break
-    return None if best is None else (best[1], best[2])
+        ttft_c = k_c * l + d_c
+        ttft_d = ttft_c + (delta - d_c) + k_d * r * l
+        lo = (k_d * r * l - ttft_c) / (tau - tpot_d)          # smoothed-TPOT bound on L - 1
+        hi = (ttft_d - ttft_c) / tpot_c                       # cloud-occupation bound on L - 1
+        L = max(2, ceil(lo) + 1)                              # smallest integer L > 1 with L - 1 >= lo
+        if L - 1 <= hi and L <= L_max and (best is None or ttft_d < best[0]):
+            best = (ttft_d, r, L)
+    return None if best is None else (float(best[1]), best[2])

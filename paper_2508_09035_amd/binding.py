@@ -24,7 +24,7 @@ class PddError(RuntimeError):
 class RLModel(ctypes.Structure):
     """Mirror of pdd_rl_model."""
     _fields_ = [(n, ctypes.c_double) for n in
-                ("k_c", "k_d", "delta", "xi_scene", "tpot_c", "tpot_d", "tau")]
+                ("k_c", "k_d", "delta", "xi_scene", "tpot_c", "tpot_d", "tau", "delta_cloud")]
 
 
 class AttnDesc(ctypes.Structure):
@@ -267,10 +267,10 @@ def aggregate_scores(scores, out, layer_weights=None, reduce_heads=False, accumu
         _ptr(layer_weights), int(bool(reduce_heads)), int(bool(accumulate)), _ptr(out), _stream()))
 
 
-def choose_r_L(l, k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau):
+def choose_r_L(l, k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau, delta_cloud=0.0):
     """pdd_choose_r_L (host only): closed-form (r, L) of the paper's program P; raises PddError
     when the constraints admit no solution."""
-    m = RLModel(k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau)
+    m = RLModel(k_c, k_d, delta, xi_scene, tpot_c, tpot_d, tau, delta_cloud)
     r, L = ctypes.c_double(), ctypes.c_int32()
     _check(load_library().pdd_choose_r_L(ctypes.byref(m), int(l), ctypes.byref(r), ctypes.byref(L)))
     return r.value, L.value

@@ -19,7 +19,7 @@ struct PackParams {
     const uint8_t *mask;      // [rows, total_k]
     uint8_t *bits;            // [rows, total_bytes]
     const int32_t *cu_k;      // [B+1]
-    const int32_t *cu_bytes;  // [B+1], cu_bytes[b+1] - cu_bytes[b] >= ceil(Nk_b / 8)
+    const int32_t *cu_bytes;  // [B+1] byte offsets of the sequences' streams inside a row
     int32_t rows, B, total_k, total_bytes;
 };
 
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_mask_kernel(const PackParam
     const int nk = ke - ks;
     const int b0 = min(max(p.cu_bytes[b], 0), p.total_bytes);
     const int b1 = min(max(p.cu_bytes[b + 1], b0), p.total_bytes);
-    const int nbytes = b1 - b0;                       // bytes reserved for this sequence
+    const int nbytes = min(b1 - b0, (nk + 7) / 8);    // bytes written: what the sequence needs, inside its span
     const int j = blockIdx.x * kPackThreads + threadIdx.x;       // output byte = tokens 8j .. 8j+7
     if (j >= nbytes) return;
     const uint8_t *src = p.mask + (int64_t)r * p.total_k + ks;

@@ -4,6 +4,7 @@
 #include "../../include/pdd.h"
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -16,12 +17,12 @@
 #include "pack_mask.hpp"
 #include "select_sentences.hpp"
 #include "aggregate.hpp"
-#include <cmath>
+#include <mutex>
 
 namespace {
 
 thread_local char g_err[512] = "";
-int g_attn_waves = 0;  // 0 = choose per problem
+std::atomic<int> g_attn_waves{0};  // 0 = choose per problem
 
 pdd_status fail(pdd_status st, const char *fmt, ...)
 {
@@ -99,15 +100,33 @@ float scale_log2(const pdd_attn_desc *d)
     return s * 1.4426950408889634f;
 }
 
+// The dynamic-LDS limit of a kernel is raised once per (kernel, device), not on every launch.
+pdd_status raise_lds_limit(const void *kern, int bytes)
+{
+    struct Done { const void *kern; int dev; };
+    static Done done[64];
+    static int n_done = 0;
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < n_done; ++i)
+        if (done[i].kern == kern && done[i].dev == dev) return PDD_OK;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    if (n_done < 64) done[n_done++] = {kern, dev};
+    return PDD_OK;
+}
+
 template <typename Kern>
 pdd_status launch_attn_kernel(Kern kern, int smem, int threads, const pdd::AttnParams &p, int64_t blocks,
                               hipStream_t st)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    const pdd_status s = raise_lds_limit(reinterpret_cast<const void *>(kern), smem);
+    if (s) return s;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), smem, st, p);
-    e = hipGetLastError();
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(PDD_ERR_HIP, "attention launch: %s", hipGetErrorString(e));
     return PDD_OK;
 }
@@ -367,9 +386,9 @@ pdd_status pdd_select_sentences(const float *scores, int32_t n_heads, int32_t ba
     p.s_cap = max_sent_per_seq > 0 ? ((max_sent_per_seq + 3) & ~3) : 4;
     p.mode = agg_mode == PDD_SENT_MEAN ? pdd::kSentMean : pdd::kSentSum;
     const int smem = p.s_cap * 16;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pdd::select_sentences_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, pdd::kSentMax * 16);
-    if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    s = raise_lds_limit(reinterpret_cast<const void *>(pdd::select_sentences_kernel), pdd::kSentMax * 16);
+    if (s) return s;
+    hipError_t e;
     hipLaunchKernelGGL(pdd::select_sentences_kernel, dim3((unsigned)batch, (unsigned)n_heads),
                        dim3(pdd::kSelThreads), smem, (hipStream_t)stream, p);
     e = hipGetLastError();
@@ -410,22 +429,32 @@ pdd_status pdd_choose_r_L(const pdd_rl_model *m, int32_t l, double *r_out, int32
     if (!(m->k_c >= 0) || !(m->k_d > 0) || !(m->delta >= 0) || !(m->tpot_c > 0) || !(m->tpot_d > 0) ||
         !(m->xi_scene >= 0 && m->xi_scene <= 1))
         return fail(PDD_ERR_INVALID_ARG, "model coefficients out of range");
+    if (!(m->delta_cloud >= 0 && m->delta_cloud <= m->delta))
+        return fail(PDD_ERR_INVALID_ARG, "delta_cloud must lie in [0, delta]");
     if (!(m->tau > m->tpot_d)) return fail(PDD_ERR_INFEASIBLE, "tau must exceed the device TPOT");
     const double len = (double)l;
-    /* the objective grows with r, so the smallest admissible ratio is optimal */
-    const double r = m->xi_scene;
-    const double r_max = 1.0 - (m->k_c + m->delta / len) / m->k_d;
-    if (r > r_max) return fail(PDD_ERR_INFEASIBLE, "no ratio in [xi_scene, %.6g]", r_max);
-    const double ttft_c = m->k_c * len;
-    const double prefill_d = m->k_d * r * len;
-    const double ttft_d = ttft_c + m->delta + prefill_d;
-    const double lo = (prefill_d - ttft_c) / (m->tau - m->tpot_d);
-    const double hi = (ttft_d - ttft_c) / m->tpot_c;
-    /* smallest integer L >= 2 with L - 1 >= lo */
-    double lm1 = std::ceil(lo);
-    if (lm1 < 1.0) lm1 = 1.0;
-    if (lm1 > hi) return fail(PDD_ERR_INFEASIBLE, "no L with %.6g <= L - 1 <= %.6g", lo, hi);
-    if (lm1 > 2147483646.0) return fail(PDD_ERR_INFEASIBLE, "L out of range");
+    /* In terms of x = k_d*r*l (device prefill time of the refined prompt) and n = L - 1 >= 1:
+     *   Eq. 5: x_min = k_d*xi*l <= x <= x_max = k_d*l - k_c*l - delta
+     *   Eq. 6: n*tpot_c - (delta - delta_cloud) <= x <= n*(tau - tpot_d) + TTFT_c
+     * The objective grows with x.  Below n0 = the smallest n whose upper bound reaches x_min
+     * nothing is feasible; from n0 on the lower bound only grows with n, so the optimum is
+     * n0 with x = max(x_min, n0*tpot_c - decompress), if that still respects both upper bounds. */
+    const double ttft_c = m->k_c * len + m->delta_cloud;          /* prefill + compress + RTT */
+    const double decompress = m->delta - m->delta_cloud;
+    const double a = m->tau - m->tpot_d;
+    const double x_min = m->k_d * m->xi_scene * len;
+    const double x_max = m->k_d * len - m->k_c * len - m->delta;
+    if (x_min > x_max) return fail(PDD_ERR_INFEASIBLE, "no ratio in [xi_scene, %.6g]", x_max / (m->k_d * len));
+    double n0 = std::ceil((x_min - ttft_c) / a);
+    if (n0 < 1.0) n0 = 1.0;
+    if (n0 > 2147483646.0) return fail(PDD_ERR_INFEASIBLE, "L out of range");
+    double x = n0 * m->tpot_c - decompress;
+    double r = x / (m->k_d * len);
+    if (x <= x_min) { x = x_min; r = m->xi_scene; }
+    if (x > x_max || x > n0 * a + ttft_c)
+        return fail(PDD_ERR_INFEASIBLE, "no (r, L): L - 1 = %.0f needs a device prefill of %.6g, allowed at most %.6g",
+                    n0, x, x_max < n0 * a + ttft_c ? x_max : n0 * a + ttft_c);
+    const double lm1 = n0;
     *r_out = r;
     *L_out = (int32_t)lm1 + 1;
     return PDD_OK;

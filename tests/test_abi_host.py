@@ -124,25 +124,46 @@ def test_choose_r_L_against_exhaustive_search():
     """Host-only entry point: the closed form must agree with the oracle's search of program P."""
     import oracle
     rng = np.random.default_rng(5)
-    n_feasible = n_infeasible = 0
-    for _ in range(60):
-        c = dict(l=int(rng.integers(64, 40000)), k_c=float(rng.uniform(0.005, 0.2)),
-                 k_d=float(rng.uniform(0.1, 1.0)), delta=float(rng.uniform(0, 800)),
-                 xi_scene=float(rng.integers(1, 19)) / 20, tpot_c=float(rng.uniform(10, 60)),
-                 tpot_d=float(rng.uniform(30, 90)), tau=float(rng.uniform(95, 200)))
-        want = oracle.choose_r_L(**c)
+    n_feasible = n_infeasible = n_moved = 0
+    for it in range(100):
+        if it < 60:         # long prompts: the quality bound xi_scene is the optimum whenever P is feasible
+            c = dict(l=int(rng.integers(64, 40000)), k_c=float(rng.uniform(0.005, 0.2)),
+                     k_d=float(rng.uniform(0.1, 1.0)), delta=float(rng.uniform(0, 800)),
+                     xi_scene=float(rng.integers(1, 19)) / 20, tpot_c=float(rng.uniform(10, 60)),
+                     tpot_d=float(rng.uniform(30, 90)), tau=float(rng.uniform(95, 200)))
+        else:               # short prompts: the cloud-occupation bound often pushes r above xi_scene
+            c = dict(l=int(rng.integers(40, 400)), k_c=float(rng.uniform(0.005, 0.1)),
+                     k_d=float(rng.uniform(0.3, 1.0)), delta=float(rng.uniform(0, 10)),
+                     xi_scene=float(rng.integers(1, 8)) / 20, tpot_c=float(rng.uniform(10, 60)),
+                     tpot_d=float(rng.uniform(30, 90)), tau=float(rng.uniform(95, 200)))
+        c["delta_cloud"] = float(rng.uniform(0, 1)) * c["delta"] if rng.random() < 0.7 else 0.0
+        want = oracle.choose_r_L(**c, L_max=8000 if it < 60 else 1000)
         if want is None:
             with pytest.raises(pdd.PddError) as e:
                 pdd.choose_r_L(**c)
             assert e.value.status == -5
             n_infeasible += 1
         else:
-            assert pdd.choose_r_L(**c) == want
+            got = pdd.choose_r_L(**c)
+            assert got[1] == want[1] and abs(got[0] - want[0]) <= 1e-12 * want[0]
             n_feasible += 1
-    assert n_feasible >= 10 and n_infeasible >= 5
+            n_moved += want[0] > c["xi_scene"] * (1 + 1e-9)
+    assert n_feasible >= 10 and n_infeasible >= 5 and n_moved >= 3
     with pytest.raises(pdd.PddError) as e:
         pdd.choose_r_L(0, 0.02, 0.5, 300, 0.6, 30, 50, 100)
     assert e.value.status == -1
+    with pytest.raises(pdd.PddError) as e:                        # delta_cloud is a part of delta
+        pdd.choose_r_L(100, 0.02, 0.5, 300, 0.6, 30, 50, 100, delta_cloud=301)
+    assert e.value.status == -1
+    # the split of delta decides feasibility (hand-worked in the oracle's pins)
+    tight = dict(l=100, k_c=0.3, k_d=0.5, delta=5, xi_scene=0.2, tpot_c=12, tpot_d=50, tau=100)
+    assert pdd.choose_r_L(**tight) == (0.2, 2)
+    r, L = pdd.choose_r_L(**tight, delta_cloud=5)                 # xi_scene infeasible, 0.24 is the optimum
+    assert abs(r - 0.24) < 1e-15 and L == 2
+    with pytest.raises(pdd.PddError) as e:
+        pdd.choose_r_L(**dict(tight, tpot_c=16), delta_cloud=5)
+    assert e.value.status == -5
+    assert pdd.choose_r_L(8192, 0.02, 0.5, 300, 0.6, 30, 50, 100, delta_cloud=200) == (0.6, 43)
     with pytest.raises(pdd.PddError) as e:                        # tau must exceed the device TPOT
         pdd.choose_r_L(100, 0.02, 0.5, 300, 0.6, 30, 50, 50)
     assert e.value.status == -5

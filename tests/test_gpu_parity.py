@@ -4,6 +4,8 @@ same seeded inputs.
 Tolerances: O max-abs <= 2e-2 (bf16 output); log-sum-exp and importance
 <= 1e-3 relative (|a-b| <= 1e-3*max(|b|,1e-6)); index sets exact except at
 ties (see check_selection)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -221,6 +223,41 @@ def test_select_long_rows_beyond_lds_staging():
     _select_case(s, lens, [1, 33000])
 
 
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c5", "c4"])
+def test_gate_a_oracle_scores_of_every_configuration(name):
+    """The oracle's importance of each benchmark configuration, rounded to fp32, through the GPU
+    selection with that configuration's own candidate ranges and k: the set must be the
+    oracle's, except inside the 1e-6 relative tie band.  The row lengths 512 / 4096, 7898,
+    8448 and 32768 take the register-resident kernel with 4, 8, 16 and 32 keys per thread."""
+    wl = W.make_workload(name)
+    window = -1 if wl.chunked else wl.window
+    oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, window)
+    dev = DeviceWorkload(wl)
+    dev.poison()
+    s32 = oI.astype(np.float32)
+    dev.select(scores=torch.from_numpy(s32).cuda())
+    torch.cuda.synchronize()
+    idx, mask = dev.idx.cpu().numpy(), dev.mask.cpu().numpy()
+    check_selection(s32.astype(np.float64), idx, mask, wl, -1, f"{name} gate A fp32")
+    swapped = check_selection(oI, idx, mask, wl, 1e-6, f"{name} gate A fp64")
+    print(f"{name}: gate A swapped inside the tie band: {swapped}")
+
+
+@pytest.mark.parametrize("n", [3000, 4096, 8000, 16384, 20000, 32768])
+def test_select_exact_in_every_register_variant(n):
+    """Exact selection (ties, candidate ranges, k = 0 / everything) at row lengths that take the
+    register-resident kernel with 4, 8, 16 and 32 keys per thread."""
+    rng = np.random.default_rng(n)
+    lens = [n, 1, n // 3]
+    tot = sum(lens)
+    s = rng.integers(0, 200, size=(3, tot)).astype(np.float64) / 16.0      # many exact ties
+    s[1] = rng.standard_normal(tot) ** 3
+    s[2, : n // 2] = 0.125                                                   # a long plateau
+    _select_case(s, lens, [n // 10, 1, n // 6])
+    _select_case(s, lens, [n, 0, 1])
+    _select_case(s, lens, [n // 4, 1, 5], cand=([7, 0, 1], [n - 5, 1, n // 3 - 1]))
+
+
 # ------------------------------------------------------ benchmark configurations
 def test_c2_llama_layer_full():
     wl = W.make_workload("c2")
@@ -229,13 +266,14 @@ def test_c2_llama_layer_full():
     assert swapped == 0
 
 
-def _sample_rows(wl, per_seq_random, tile=256, seed=0):
+def _sample_rows(wl, per_seq_random, tile=256, seed=0, first=64):
+    """Window rows, the first `first` rows, every `tile`-row boundary +- 1 and seeded random rows."""
     rng = np.random.default_rng(seed)
     rows = []
     for b in range(wl.batch):
         qs, nq = int(wl.cu_seqlens_q[b]), int(wl.seqlens_q[b])
         w = nq if wl.chunked else min(wl.window, nq)
-        loc = set(range(nq - w, nq)) | set(range(min(nq, 64)))
+        loc = set(range(nq - w, nq)) | set(range(min(nq, first)))
         for t in range(tile, nq, tile):
             loc |= {t - 1, t, t + 1} & set(range(nq))
         loc |= set(int(x) for x in rng.integers(0, nq, size=per_seq_random))
@@ -261,10 +299,43 @@ def test_c3_ragged_batch_sampled_rows():
 
 
 def test_c4_long_prompt_sampled_rows():
+    """O and log-sum-exp on every window row, the first 256 rows, every 256-row workgroup
+    boundary +- 1 and 2048 seeded random rows (all 32 heads each); importance and the
+    selection in full."""
     wl = W.make_workload("c4")
-    rows = _sample_rows(wl, 128, tile=2048)
+    rows = _sample_rows(wl, 2048, tile=256, first=256)
     o_err, swapped = run_and_compare(wl, rows=rows)
     print(f"c4: {len(rows)} rows, O err {o_err:.4f}, swapped {swapped}")
+    assert swapped == 0
+
+
+@pytest.mark.skipif(os.environ.get("PDD_FULL_C4") != "1",
+                    reason="about 10 minutes of fp64 oracle time; set PDD_FULL_C4=1")
+def test_c4_long_prompt_every_row():
+    """Every row of the 32k-token configuration against the oracle, in chunks that print
+    their progress."""
+    wl = W.make_workload("c4")
+    dev = DeviceWorkload(wl)
+    dev.poison()
+    dev.step()
+    O, lse, imp, idx, mask = dev.results()
+    worst_o, worst_l = 0.0, 0.0
+    step = 1024
+    for r0 in range(0, wl.total_q, step):
+        rows = np.arange(r0, min(r0 + step, wl.total_q), dtype=np.int32)
+        oO, oL = oracle.attention(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, rows=rows)
+        worst_o = max(worst_o, float(np.abs(O[rows] - oO).max()))
+        rel = np.abs(lse[:, rows] - oL) / np.maximum(np.abs(oL), 1e-6)
+        worst_l = max(worst_l, float(rel.max()))
+        print(f"c4 full: rows {r0}..{rows[-1]}: O max-abs {worst_o:.4g}, lse rel {worst_l:.3g}", flush=True)
+        assert worst_o <= O_ATOL and worst_l <= REL
+    oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, wl.window)
+    rel_close(imp, oI, "c4 full importance")
+    swapped = check_selection(oI, idx, mask, wl, REL, "c4 full select")
+    irel = float((np.abs(imp - oI) / np.maximum(np.abs(oI), 1e-6)).max())
+    print(f"c4 full: O max-abs {worst_o:.4g}, lse rel {worst_l:.3g}, importance rel {irel:.3g}, "
+          f"gate-B swaps {swapped}", flush=True)
+    assert swapped == 0
 
 
 def test_c4h_heavy_hitters_are_selected():
@@ -274,7 +345,7 @@ def test_c4h_heavy_hitters_are_selected():
     wl = W.make_workload("c4h", n_override=8192)
     dev = DeviceWorkload(wl)
     dev.step()
-    _, swapped = compare_all(wl, dev, rows=_sample_rows(wl, 32, tile=2048), label="c4h")
+    _, swapped = compare_all(wl, dev, rows=_sample_rows(wl, 32), label="c4h")
     idx = dev.idx.cpu().numpy()
     heavy = wl.extra["heavy_positions"]
     for g in range(wl.n_kv_heads):
@@ -316,18 +387,31 @@ def test_pack_mask_bit_exact():
 
 
 # ------------------------------------------------------------------ 1-D pooling
+# Row lengths per case: the longest row decides the kernel for the whole launch, so each case
+# stays inside one class: register-resident with 4 / 8 / 16 / 32 keys per thread (longest row
+# <= 4096 / 8192 / 16384 / 32768), or the radix kernel for longer rows.
+_POOL_CASES = {
+    "reg4": ([700, 3, 1, 4096], [70, 2, 1, 1500], [10, 0, 0, 0], [690, 3, 1, 4096]),
+    "reg8": ([700, 3, 1, 5000], [70, 2, 1, 1500], [10, 0, 0, 0], [690, 3, 1, 5000]),
+    "reg16": ([12000, 1, 9000], [1200, 1, 4500], [0, 0, 100], [12000, 1, 8000]),
+    "reg32": ([30000, 2, 17000], [3000, 1, 17000], [5, 0, 0], [29990, 2, 17000]),
+    "radix": ([700, 3, 40000], [70, 2, 4000], [10, 0, 100], [690, 3, 39000]),
+}
+
+
 @pytest.mark.parametrize("mode,kernel", [("max", 5), ("avg", 7), ("avg", 1), ("max", 33)])
-def test_pooled_selection(mode, kernel):
+@pytest.mark.parametrize("case", list(_POOL_CASES))
+def test_pooled_selection(case, mode, kernel):
+    lens, keep, cb, ce = _POOL_CASES[case]
     rng = np.random.default_rng(11)
-    lens = [700, 3, 1, 5000, 40000]                 # the last row takes the long-row kernel
     heads = 2
     s32 = (rng.random((heads, sum(lens))) ** 6).astype(np.float32)
     s32[1, 100:140] = 0.5                           # a plateau: ties after max pooling
     wl = W.make_custom("t", lens, None, 1, 1, 64, 0, seed=0)
     wl.n_kv_heads = heads
-    wl.k_keep = np.array([70, 2, 1, 1500, 4000], dtype=np.int32)
-    wl.cand_begin = np.array([10, 0, 0, 0, 100], dtype=np.int32)
-    wl.cand_end = np.array([690, 3, 1, 5000, 39000], dtype=np.int32)
+    wl.k_keep = np.array(keep, dtype=np.int32)
+    wl.cand_begin = np.array(cb, dtype=np.int32)
+    wl.cand_end = np.array(ce, dtype=np.int32)
     want_pooled = oracle.pool_scores(s32.astype(np.float64), wl.cu_seqlens_k, kernel, mode)
     dev = DeviceWorkload(wl)
     dev.poison()
@@ -357,6 +441,26 @@ def _sentence_split(rng, lo, hi, mean_len, with_empty):
         if with_empty and rng.random() < 0.05:
             ends.append(x)
     return ends
+
+
+def _oracle_keep_on_kernel_scores(got_sc, cu, cu_sent, ends, budget, cb):
+    """The oracle's sentence ranking applied to the fp32 sentence scores the kernel ranked: a
+    token-score array that holds each sentence's score on its first token and zero elsewhere
+    sums (mode "sum") to exactly that score, so oracle.select_sentences ranks the kernel's own
+    values with the real sentence lengths and budget."""
+    H = got_sc.shape[0]
+    tok = np.zeros((H, int(cu[-1])), dtype=np.float64)
+    for b in range(len(cu) - 1):
+        start = int(cb[b])
+        for s_ in range(cu_sent[b], cu_sent[b + 1]):
+            if ends[s_] > start:
+                tok[:, cu[b] + start] = got_sc[:, s_]
+            else:
+                assert (got_sc[:, s_] == 0).all()           # an empty sentence scores zero
+            start = int(ends[s_])
+    sc, keep, mask, kept = oracle.select_sentences(tok, cu, cu_sent, ends, budget, "sum", cb)
+    assert np.array_equal(sc, got_sc)
+    return keep, mask, kept
 
 
 @pytest.mark.parametrize("mode", ["sum", "mean"])
@@ -401,31 +505,12 @@ def test_select_sentences(mode, exact_scores):
     if exact_scores and mode == "sum":
         assert np.array_equal(got_sc, want_sc)
         assert np.array_equal(skeep.cpu().numpy(), want_keep)
-    # the decision is exact on the sentence scores the kernel ranked (fp32, as the kernel holds them):
-    # the ranking rule of the oracle applied to those scores, one token-score row per sentence
-    ln = np.concatenate([np.diff(np.concatenate([[cb[b]], ends[cu_sent[b]:cu_sent[b + 1]]]))
-                         for b in range(len(lens))]).astype(np.int64)
-    for g in range(heads):
-        for b in range(len(lens)):
-            sl = slice(cu_sent[b], cu_sent[b + 1])
-            sc_b, ln_b = got_sc[g, sl], ln[sl]
-            order = np.lexsort((np.arange(len(sc_b)), -sc_b))
-            fit = np.cumsum(ln_b[order]) <= budget[b]
-            m = int(fit.sum()) if fit.all() else int(np.argmin(fit))
-            want = np.zeros(len(sc_b), dtype=np.uint8)
-            want[order[:m]] = 1
-            assert np.array_equal(skeep.cpu().numpy()[g, sl], want), (g, b)
-            assert int(kept.cpu().numpy()[g, b]) == int(ln_b[want == 1].sum()) <= budget[b]
-    # token mask = expansion of the keep flags
-    want_m = np.zeros_like(want_mask)
+    # the decision is exact on the sentence scores the kernel ranked (fp32, as the kernel holds them)
     kf = skeep.cpu().numpy()
-    for g in range(heads):
-        for b in range(len(lens)):
-            st = int(cb[b])
-            for s in range(cu_sent[b], cu_sent[b + 1]):
-                want_m[g, cu[b] + st: cu[b] + ends[s]] = kf[g, s]
-                st = int(ends[s])
-    assert np.array_equal(mask.cpu().numpy(), want_m)
+    x_keep, x_mask, x_kept = _oracle_keep_on_kernel_scores(got_sc, cu, cu_sent, ends, budget, cb)
+    assert np.array_equal(kf, x_keep)
+    assert np.array_equal(mask.cpu().numpy(), x_mask)             # token mask = expansion of the flags
+    assert np.array_equal(kept.cpu().numpy(), x_kept) and (x_kept <= budget[None, :]).all()
     # against the fp64 oracle: identical up to sentences whose scores tie within fp32 rounding
     diff = kf != want_keep
     if diff.any():
@@ -508,19 +593,13 @@ def test_refinement_pipeline_end_to_end():
     np.testing.assert_allclose(sscore.cpu().numpy().astype(np.float64), w_sc, rtol=2e-6, atol=1e-12)
     # the decision, on the sentence scores the kernel ranked
     g_sc = sscore.cpu().numpy().astype(np.float64)
+    x_keep, x_mask, x_kept = _oracle_keep_on_kernel_scores(g_sc, wl.cu_seqlens_k, cu_sent, ends, budget, cb)
+    assert np.array_equal(skeep.cpu().numpy(), x_keep)
+    assert np.array_equal(mask.cpu().numpy(), x_mask)
+    assert np.array_equal(kept.cpu().numpy(), x_kept) and (x_kept <= budget[None, :]).all()
     for b in range(2):
-        sl = slice(cu_sent[b], cu_sent[b + 1])
-        e = ends[sl]
-        ln = np.diff(np.concatenate([[cb[b]], e]))
-        order = np.lexsort((np.arange(len(e)), -g_sc[0, sl]))
-        fit = np.cumsum(ln[order]) <= budget[b]
-        m = int(fit.sum()) if fit.all() else int(np.argmin(fit))
-        want = np.zeros(len(e), dtype=np.uint8)
-        want[order[:m]] = 1
-        assert np.array_equal(skeep.cpu().numpy()[0, sl], want)
-        assert int(kept.cpu().numpy()[0, b]) == int(ln[want == 1].sum()) <= budget[b]
         seq = mask.cpu().numpy()[0, wl.cu_seqlens_k[b]:wl.cu_seqlens_k[b + 1]]
-        assert seq[:20].sum() == 0 and seq[int(lens[b]) - 12:].sum() == 0 and seq.sum() == int(ln[want == 1].sum())
+        assert seq[:20].sum() == 0 and seq[int(lens[b]) - 12:].sum() == 0 and seq.sum() == int(x_kept[0, b])
     # bit stream of the token mask
     want_bits, cu_bytes = oracle.pack_mask(mask.cpu().numpy(), wl.cu_seqlens_k)
     bits = torch.empty((1, int(cu_bytes[-1])), dtype=torch.uint8, device="cuda")

@@ -455,6 +455,20 @@ def test_choose_r_L_search_matches_closed_form():
         assert got[0] == c["xi_scene"] and got[1] == 1 + max(1, math.ceil(lo))
     # worked numbers for the first case: prefill_d = 2457.6, TTFT_c = 163.84 -> (2293.76 / 50) = 45.9 -> L = 47
     assert oracle.choose_r_L(**cases[0]) == (0.6, 47)
+    # the part of delta spent before the first token arrives (compress + RTT, Eq. 2) delays TTFT_c:
+    # TTFT_c = 163.84 + 200 -> (2457.6 - 363.84) / 50 = 41.875 -> L = 43; the cloud-occupation bound
+    # is (decompress + prefill_d) / TPOT_c = (100 + 2457.6) / 30 = 85.25 (Eq. 3, Eq. 6)
+    assert oracle.choose_r_L(**cases[0], delta_cloud=200) == (0.6, 43)
+    # a case the split decides: prefill_d(rl) = 10, lower bound <= 0 -> L - 1 = 1; the upper bound is
+    # (5 - delta_cloud + 10) / 12: 1.25 with delta_cloud = 0 (feasible, L = 2), 0.83 with delta_cloud = 5
+    tight = dict(l=100, k_c=0.3, k_d=0.5, delta=5, xi_scene=0.2, tpot_c=12, tpot_d=50, tau=100)
+    assert oracle.choose_r_L(**tight) == (0.2, 2)
+    # with delta_cloud = 5 the ratio xi_scene = 0.2 is infeasible, but P is not: the bound 0.5 r 100 / 12 >= 1
+    # holds from r = 0.24 on (Eq. 5 allows r <= 1 - (0.3 + 0.05) / 0.5 = 0.3), so the optimum moves there
+    assert oracle.choose_r_L(**tight, delta_cloud=5) == (0.24, 2)
+    assert oracle.choose_r_L(**dict(tight, tpot_c=16), delta_cloud=5) is None       # would need r = 0.32 > 0.3
+    # off-grid optimum: tpot_c = 12.3 -> r = 12.3 / 50 = 0.246
+    assert oracle.choose_r_L(**dict(tight, tpot_c=12.3), delta_cloud=5) == (float(__import__("fractions").Fraction(12.3) / 50), 2)
     # Eq. 5 empty: the cloud is too slow relative to the device
     assert oracle.choose_r_L(8192, 0.4, 0.5, 300, 0.6, 30, 50, 100) is None
     # Eq. 6 empty: the smoothing needs more cloud tokens than the occupation bound allows
