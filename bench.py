@@ -4,9 +4,15 @@ One "step" = one pass of the whole path over one synthetic batch: fused causal
 prefill attention + observation-window importance, then top-k selection with
 index compaction.  Inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line (see the field notes at the bottom of this file).
+Prints ONE JSON line (see the field notes at the bottom of this file).  The
+top-level fields are those of the 32k-token prompt (the configuration the
+target is quoted on); `configs` carries the same measurements for the other
+four configurations.  Every configuration is also compared with the CPU
+oracle on the same tensors in the same run (`parity`); a mismatch makes the
+benchmark exit with status 1.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -14,16 +20,19 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+HEADLINE = "c4"
+OTHERS = ("c1", "c2", "c3", "c5")
 
 # HBM bytes per launch of the attention kernel (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc runs, each
 # scaled by the same counter's reading for a 1 GiB device copy; see profiles/).  Valid only for the
 # kernel sources with this digest: once they change the figure is reported as null.
 KERNEL_SOURCES = ("attn_fwd_d128.hpp", "attn_fwd.hpp")
 TRAFFIC = {"c4": {"bytes": 1.679e9, "sources_sha256": "1009c1eeac8510839fc7860fac20275dbe402f28f8df4b6574fd7eb6dd409668"}}
+
+O_ATOL, REL = 2e-2, 1e-3       # the parity bar: O max-abs, log-sum-exp / importance relative
 
 
 def kernel_digest():
@@ -36,6 +45,7 @@ def kernel_digest():
 
 
 def time_gpu(fn, iters, warmup):
+    """Average milliseconds per call between two HIP events on the stream the calls are enqueued on."""
     import torch
     for _ in range(warmup):
         fn()
@@ -46,21 +56,19 @@ def time_gpu(fn, iters, warmup):
         fn()
     stop.record()
     torch.cuda.synchronize()
-    return start.elapsed_time(stop) / iters     # ms
+    return start.elapsed_time(stop) / iters
 
 
-def cpu_baseline(wl, budget_gflop=200.0):
-    """Time the oracle (as it stands) on a bounded seeded sample of query rows
-    of the same workload, on the host cores."""
+def oracle_sample(wl, budget_gflop):
+    """The oracle (as it stands) on a bounded seeded sample of query rows of the workload, timed on
+    the host cores.  Returns the rows, its O and log-sum-exp for them, the flops and the seconds."""
     import numpy as np
     import oracle
     d, hq = wl.head_dim, wl.n_q_heads
     rng = np.random.default_rng(1234)
     rows, flops = [], 0.0
-    total_q = wl.total_q
-    order = rng.permutation(total_q)
     cu_q, cu_k = wl.cu_seqlens_q, wl.cu_seqlens_k
-    for r in order:
+    for r in rng.permutation(wl.total_q):
         b = int(np.searchsorted(cu_q, r, side="right") - 1)
         i = int(r - cu_q[b])
         n_vis = i + int((cu_k[b + 1] - cu_k[b]) - (cu_q[b + 1] - cu_q[b])) + 1
@@ -70,12 +78,143 @@ def cpu_baseline(wl, budget_gflop=200.0):
             break
     rows = np.array(sorted(rows), dtype=np.int32)
     t0 = time.perf_counter()
-    oracle.attention(wl.q, wl.k, wl.v, cu_q, cu_k, wl.scale, rows=rows)
-    dt = time.perf_counter() - t0
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle",
-            "sample": f"{len(rows)} seeded random query rows x {hq} heads of {wl.name} "
-                      f"({flops / 1e9:.1f} GFLOP of attention, fp64, {dt:.1f} s)"}
+    oO, oL = oracle.attention(wl.q, wl.k, wl.v, cu_q, cu_k, wl.scale, rows=rows)
+    return rows, oO, oL, flops, time.perf_counter() - t0
+
+
+def parity(wl, dev, rows, oO, oL):
+    """The outputs of one step against the oracle: O and log-sum-exp on the sampled rows,
+    importance and the selected index sets in full (indices may differ only where the oracle's
+    score lies within the score tolerance of the k-th score)."""
+    import numpy as np
+    import oracle
+    dev.poison()
+    dev.step()
+    O, lse, imp, idx, mask = dev.results()
+    o_err = float(np.abs(O[rows] - oO).max()) if len(rows) else 0.0
+    l_rel = float((np.abs(lse[:, rows] - oL) / np.maximum(np.abs(oL), 1e-6)).max()) if len(rows) else 0.0
+    oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale,
+                           -1 if wl.chunked else wl.window)
+    i_rel = float((np.abs(imp - oI) / np.maximum(np.abs(oI), 1e-6)).max())
+    want_idx, want_mask = oracle.select_topk(oI, wl.cu_seqlens_k, wl.k_keep, wl.cand_begin, wl.cand_end)
+    cu_keep = wl.cu_keep
+    beyond_ties = tie_swaps = 0
+    for g in range(wl.n_kv_heads):
+        for b in range(wl.batch):
+            got, want = idx[g, cu_keep[b]:cu_keep[b + 1]], want_idx[g, cu_keep[b]:cu_keep[b + 1]]
+            if np.array_equal(got, want):
+                continue
+            row = oI[g, wl.cu_seqlens_k[b]:wl.cu_seqlens_k[b + 1]]
+            tau = row[want].min()
+            for j in np.setxor1d(got, want):
+                if 0 <= j < len(row) and abs(row[j] - tau) <= REL * abs(tau):
+                    tie_swaps += 1
+                else:
+                    beyond_ties += 1
+    mask_ok = bool(np.array_equal(mask.sum(axis=1), np.full(wl.n_kv_heads, int(wl.k_keep.sum()))))
+    finite = bool(np.isfinite(O).all() and np.isfinite(lse).all() and np.isfinite(imp).all())
+    ok = finite and o_err <= O_ATOL and l_rel <= REL and i_rel <= REL and beyond_ties == 0 and mask_ok
+    return {"ok": bool(ok), "rows_checked": int(len(rows)), "o_max_abs": round(o_err, 5),
+            "lse_rel": float(f"{l_rel:.3g}"), "importance_rel": float(f"{i_rel:.3g}"),
+            "index_diffs_beyond_ties": beyond_ties, "index_swaps_inside_ties": tie_swaps}
+
+
+def mfma_probe(iters=40000, reps=3):
+    """What the bf16 matrix pipe sustains by itself (libpdd_probe.so): TFLOP/s and the shader clock
+    during the run, on constant operands and on operands that change from one MFMA to the next."""
+    import numpy as np
+    import torch
+    path = os.path.join(ROOT, "paper_2508_09035_amd", "libpdd_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is not built; run __graft_entry__.build()")
+    lib = ctypes.CDLL(path)
+    lib.pdd_probe_operand_bytes.restype = ctypes.c_int
+    lib.pdd_probe_mfma_flops.restype = ctypes.c_double
+    lib.pdd_probe_mfma_flops.argtypes = [ctypes.c_int, ctypes.c_int]
+    lib.pdd_probe_mfma.restype = ctypes.c_int
+    lib.pdd_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    blocks = torch.cuda.get_device_properties(0).multi_processor_count
+    nbytes = lib.pdd_probe_operand_bytes()
+    rng = np.random.default_rng(7)
+    import workloads
+    bits = workloads.f32_to_bf16_bits(rng.standard_normal(nbytes // 2).astype(np.float32))
+    operands = torch.from_numpy(bits.view(np.int16)).cuda()
+    ticks = torch.zeros(2 * blocks, dtype=torch.int64, device="cuda")
+    sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream or None
+    lib.pdd_probe_wall_clock_khz.restype = ctypes.c_int
+    wall_khz = lib.pdd_probe_wall_clock_khz() or 100000
+    out = {}
+    for name, varying in (("constant_operands", 0), ("varying_operands", 1)):
+        def launch():
+            rc = lib.pdd_probe_mfma(varying, blocks, iters, operands.data_ptr(), ticks.data_ptr(),
+                                    sink.data_ptr(), stream)
+            if rc != 0:
+                raise RuntimeError(f"probe launch failed: hipError {rc}")
+        ms = time_gpu(launch, reps, 1)
+        t = ticks.cpu().numpy().reshape(blocks, 2).astype(np.float64)
+        ghz = float(np.median(t[:, 0] / np.maximum(t[:, 1], 1.0)) * wall_khz * 1e-6)
+        out[name] = {"tflops": round(lib.pdd_probe_mfma_flops(blocks, iters) / (ms * 1e-3) / 1e12, 1),
+                     "shader_clock_ghz": round(ghz, 3)}
+    return out
+
+
+def run_config(name, args, budget_gflop, with_cpu_baseline):
+    import torch
+    import workloads
+    import paper_2508_09035_amd as pdd
+    from paper_2508_09035_amd.harness import DeviceWorkload
+
+    wl = workloads.make_workload(name)
+    dev = DeviceWorkload(wl)
+    pdd.set_option(pdd.OPT_ATTN_WAVES, args.waves)
+
+    res = {}
+    if not args.no_parity:
+        rows, oO, oL, flops, dt = oracle_sample(wl, budget_gflop)
+        res["parity"] = parity(wl, dev, rows, oO, oL)
+        if with_cpu_baseline:
+            import oracle
+            res["cpu_baseline"] = {
+                "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+                "sample": f"{len(rows)} seeded random query rows x {wl.n_q_heads} heads of {wl.name} "
+                          f"({flops / 1e9:.1f} GFLOP of attention, fp64, {dt:.1f} s)"}
+
+    # whole path, then per-kernel legs (same launch configuration), HIP events on the launch stream
+    ms_step = time_gpu(dev.step, args.steps, args.warmup)
+    ms_attn = time_gpu(lambda: dev.attn(with_importance=False), args.steps, 2)
+    ms_attn_imp = time_gpu(lambda: dev.attn(with_importance=True), args.steps, 2)
+    ms_select = time_gpu(dev.select, args.steps, 2)
+
+    attn_flops, imp_flops = wl.attn_flops(), wl.importance_flops()
+    tflops_path = (attn_flops + imp_flops) / (ms_step * 1e-3) / 1e12
+    tflops_attn = attn_flops / (ms_attn * 1e-3) / 1e12
+    sel_bytes = 4 * wl.n_kv_heads * int((wl.cand_end - wl.cand_begin).sum()) \
+        + 4 * wl.n_kv_heads * int(wl.k_keep.sum()) + wl.n_kv_heads * wl.total_k
+    t = TRAFFIC.get(wl.name)
+    traffic = t["bytes"] if t and t["sources_sha256"] == kernel_digest() else None
+    res.update({
+        "value": round(tflops_path, 2),
+        "ms_per_step": round(ms_step, 4),
+        "config": {"workload": f"{wl.name}: {wl.notes}", "batch": wl.batch,
+                   "total_q": wl.total_q, "total_k": wl.total_k, "n_q_heads": wl.n_q_heads,
+                   "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "window": wl.window,
+                   "keep_ratio": str(wl.keep_ratio), "parallelism": "single GPU"},
+        "pct_bf16_mfma_peak": round(100 * tflops_path / PEAK_BF16_TFLOPS, 2),
+        "prompt_tokens_per_s": round(wl.total_q / (ms_step * 1e-3), 1),
+        "legs_ms": {"attention": round(ms_attn, 4), "attention+importance": round(ms_attn_imp, 4),
+                    "select+compaction": round(ms_select, 4)},
+        "select_GBps": round(sel_bytes / (ms_select * 1e-3) / 1e9, 2),
+        "roofline": {"bound": "mfma",
+                     "kernel": "attn_fwd_d128_kernel" if wl.head_dim == 128 else "attn_fwd_kernel",
+                     "achieved": round(tflops_attn, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 4),
+                     "traffic": traffic},
+    })
+    del dev
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -83,8 +222,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c4", help="workload: c1..c5 (default: the 32k-token prompt)")
+    ap.add_argument("--config", default="all",
+                    help="all (default): the 32k-token prompt as the headline plus the other four "
+                         "configurations under `configs`; or one of c1..c5 alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true", help="skip the in-run comparison with the oracle")
+    ap.add_argument("--no-probe", action="store_true", help="skip the matrix-pipe probe")
     ap.add_argument("--waves", type=int, default=0, help="attention waves per workgroup (0 = auto)")
     ap.add_argument("--kernel-digest", action="store_true", help="print the digest of the attention "
                     "kernel sources (the key of the stored HBM traffic figure) and exit")
@@ -100,24 +243,22 @@ def main():
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
-    import workloads
     import paper_2508_09035_amd as pdd
-    from gpu_harness import DeviceWorkload
 
     pdd.load_library()                      # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
-    wl = workloads.make_workload(args.config)
-    dev = DeviceWorkload(wl)
-    pdd.set_option(pdd.OPT_ATTN_WAVES, args.waves)
 
-    # whole path
-    ms_step = time_gpu(dev.step, args.steps, args.warmup)
-    # per-kernel legs (same launch configuration), HIP events on the launch stream
-    ms_attn = time_gpu(lambda: dev.attn(with_importance=False), args.steps, 2)
-    ms_attn_imp = time_gpu(lambda: dev.attn(with_importance=True), args.steps, 2)
-    ms_select = time_gpu(dev.select, args.steps, 2)
+    headline = HEADLINE if args.config == "all" else args.config
+    with_cpu = not args.no_cpu_baseline and not args.no_parity
+    head = run_config(headline, args, 200.0, with_cpu)
+    others = {}
+    if args.config == "all":
+        for name in OTHERS:
+            r = run_config(name, args, 15.0, False)
+            others[name] = {k: r[k] for k in ("value", "ms_per_step", "pct_bf16_mfma_peak",
+                                              "prompt_tokens_per_s", "legs_ms", "roofline", "parity")
+                            if k in r}
 
     if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
@@ -126,39 +267,31 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    attn_flops, imp_flops = wl.attn_flops(), wl.importance_flops()
-    tflops_path = (attn_flops + imp_flops) / (ms_step * 1e-3) / 1e12
-    tflops_attn = attn_flops / (ms_attn * 1e-3) / 1e12
-    sel_bytes = 4 * wl.n_kv_heads * int((wl.cand_end - wl.cand_begin).sum()) \
-        + 4 * wl.n_kv_heads * int(wl.k_keep.sum()) + wl.n_kv_heads * wl.total_k
-    t = TRAFFIC.get(wl.name)
-    traffic = t["bytes"] if t and t["sources_sha256"] == kernel_digest() else None
     out = {
         "metric": "causal prefill attn TFLOP/s (+importance) & % bf16 MFMA peak; prompt tokens/s",
-        "value": round(tflops_path, 2),
-        "unit": "TFLOP/s",
+        "value": head["value"], "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 4),
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: {wl.notes}", "batch": wl.batch,
-                   "total_q": wl.total_q, "total_k": wl.total_k, "n_q_heads": wl.n_q_heads,
-                   "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "window": wl.window,
-                   "keep_ratio": str(wl.keep_ratio), "parallelism": "single GPU"},
-        "pct_bf16_mfma_peak": round(100 * tflops_path / PEAK_BF16_TFLOPS, 2),
-        "prompt_tokens_per_s": round(wl.total_q / (ms_step * 1e-3), 1),
-        "legs_ms": {"attention": round(ms_attn, 4), "attention+importance": round(ms_attn_imp, 4),
-                    "select+compaction": round(ms_select, 4)},
-        "select_GBps": round(sel_bytes / (ms_select * 1e-3) / 1e9, 2),
-        "roofline": {"bound": "mfma",
-                     "kernel": "attn_fwd_d128_kernel" if wl.head_dim == 128 else "attn_fwd_kernel",
-                     "achieved": round(tflops_attn, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 4),
-                     "traffic": traffic},
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl)
+    for k in ("config", "pct_bf16_mfma_peak", "prompt_tokens_per_s", "legs_ms", "select_GBps", "roofline"):
+        out[k] = head[k]
+    if not args.no_probe:
+        out["roofline"]["measured_peak"] = mfma_probe()
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    ok = True
+    if not args.no_parity:
+        out["parity"] = head["parity"]
+        ok = head["parity"]["ok"] and all(o["parity"]["ok"] for o in others.values())
+        out["parity_ok"] = bool(ok)
+    if others:
+        out["configs"] = others
     print(json.dumps(out))
+    if not ok:
+        print("bench.py: the in-run comparison with the oracle FAILED (see `parity`)", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":
@@ -171,4 +304,8 @@ if __name__ == "__main__":
 #                  average duration between HIP events, against the dense bf16 MFMA peak
 #                  traffic = HBM bytes per launch from byte counters (null when not measured for
 #                  these kernel sources)
+#                  measured_peak = the matrix pipe alone (probe kernel), constant and varying operands,
+#                  with the shader clock (shader-clock ticks / wall-clock ticks of the same interval)
+#   parity         outputs of one step against the CPU oracle on the same tensors, before timing
+#   configs        the same measurements for the other configurations (not the headline)
 #   cpu_baseline   the fp64 oracle timed on a bounded sample of rows (reported, not a target)
