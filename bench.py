@@ -160,6 +160,29 @@ def mfma_probe(iters=40000, reps=3):
     return out
 
 
+def select_scaled(spec, steps):
+    """The selection kernel alone at streaming size: `rows x n` seeded fp32 scores (rows as
+    sequences of one head row, keep 1/10), algorithmic bytes = 4 B per score + 4 B per kept index +
+    1 B per mask byte."""
+    import numpy as np
+    import torch
+    import paper_2508_09035_amd as pdd
+    rows, n = (int(x) for x in spec.lower().split("x"))
+    g = torch.Generator(device="cuda").manual_seed(5)
+    scores = torch.rand((1, rows * n), generator=g, device="cuda") ** 6
+    keep = max(1, n // 10)
+    cu_k = torch.arange(0, rows + 1, dtype=torch.int32, device="cuda") * n
+    k_per = torch.full((rows,), keep, dtype=torch.int32, device="cuda")
+    cu_keep = torch.arange(0, rows + 1, dtype=torch.int32, device="cuda") * keep
+    idx = torch.empty((1, rows * keep), dtype=torch.int32, device="cuda")
+    mask = torch.empty((1, rows * n), dtype=torch.uint8, device="cuda")
+    ms = time_gpu(lambda: pdd.select_topk(scores, cu_k, n, k_per, cu_keep, rows * keep, idx, mask), steps, 2)
+    nbytes = rows * (4 * n + 4 * keep + n)
+    assert int(mask.sum().item()) == rows * keep
+    return {"select_scaled": spec, "ms": round(ms, 4), "algorithmic_bytes": nbytes,
+            "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+
+
 def run_config(name, args, budget_gflop, with_cpu_baseline):
     import torch
     import workloads
@@ -228,6 +251,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true", help="skip the in-run comparison with the oracle")
     ap.add_argument("--no-probe", action="store_true", help="skip the matrix-pipe probe")
+    ap.add_argument("--probe-only", action="store_true", help="run only the matrix-pipe probe")
+    ap.add_argument("--select-scaled", default="", metavar="ROWSxN",
+                    help="run only the selection kernel on ROWS rows of N seeded scores (streaming size)")
     ap.add_argument("--waves", type=int, default=0, help="attention waves per workgroup (0 = auto)")
     ap.add_argument("--kernel-digest", action="store_true", help="print the digest of the attention "
                     "kernel sources (the key of the stored HBM traffic figure) and exit")
@@ -248,6 +274,13 @@ def main():
 
     pdd.load_library()                      # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
+
+    if args.probe_only:
+        print(json.dumps({"measured_peak": mfma_probe()}))
+        return
+    if args.select_scaled:
+        print(json.dumps(select_scaled(args.select_scaled, args.steps)))
+        return
 
     headline = HEADLINE if args.config == "all" else args.config
     with_cpu = not args.no_cpu_baseline and not args.no_parity

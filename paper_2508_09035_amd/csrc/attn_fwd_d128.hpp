@@ -28,6 +28,7 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 constexpr int kTileBytes = kBN * 256;   // one K or V tile in LDS
 constexpr int kAttn128Bufs = 3;          // K and V tiles are triple buffered
 constexpr int kAttn128Smem = 2 * kAttn128Bufs * kTileBytes;
+constexpr float kLazyLog2 = 8.0f;        // a row's softmax reference may lag its running max by up to 2^8
 
 __device__ __forceinline__ int swz16(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
@@ -200,6 +201,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
     float m_run = -INFINITY;
     float l_part[4] = {0.f, 0.f, 0.f, 0.f};   // four interleaved partial row sums (short add chains)
     const float c2 = p.scale_log2;
+    const float lazy = kLazyLog2 / c2;         // the same distance in units of the raw scores
     float neg_mc = 0.f;                        // -m_run * c2 (0 while m_run is -inf)
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
@@ -327,10 +329,16 @@ void attn_fwd_d128_kernel(const AttnParams p)
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) l_part[e & 3] += cur[e];      // row sums: also in this phase
-        m_cand = row_max(nxt);
+        // The reference m_run of the exponentials only has to keep them in range, it need not be the
+        // exact running max: a row adopts a new reference when its max has moved by more than
+        // kLazyLog2 binary orders of magnitude (probabilities relative to the reference then stay
+        // below 2^kLazyLog2, far inside the range of fp32 sums and bf16 operands).  O and the
+        // row sums are therefore rescaled a few times per row instead of whenever a max moves.
+        const float m_true = row_max(nxt);
+        m_cand = m_true > m_run + lazy ? m_true : m_run;
         // The scale-and-subtract of the next block is done here, in the phase whose VALU is
-        // otherwise idle, against the max the next phase 1 will adopt (m_cand >= m_run, and the
-        // rescale at the start of that phase sets m_run = m_cand in the lanes where it moved).
+        // otherwise idle, against the reference the next phase 1 will adopt (m_cand >= m_run, and
+        // the rescale at the start of that phase sets m_run = m_cand in the lanes where it moved).
         premul(nxt, m_cand);
     };
     auto hot_tile = [&](auto par_c, const int it, float &m_cand) {
