@@ -106,8 +106,15 @@ enum {
  * lse        DEVICE fp32 [Hq, total_q] contiguous                      -- out
  * importance DEVICE fp32 [Hkv, total_k] contiguous, or NULL (then W is
  *            ignored); must be non-NULL when desc->window > 0          -- out
- * workspace  DEVICE scratch of at least pdd_workspace_bytes(desc,
- *            PDD_CALL_PREFILL_ATTN) bytes (may be NULL when that is 0).
+ * workspace  DEVICE scratch, 16-byte aligned, or NULL.  With at least
+ *            pdd_workspace_bytes(desc, PDD_CALL_PREFILL_ATTN) bytes the
+ *            importance step divides the window rows of every 256-key slice over
+ *            several workgroups that leave partial column sums there, added in a
+ *            fixed order afterwards; with less (or NULL) each slice is summed by
+ *            one workgroup.  Both forms are deterministic; they differ from each
+ *            other in the order of the fp32 additions.  The contents are
+ *            scratch before and after the call; concurrent calls need separate
+ *            workspaces.
  * Requires Nq_b == Nk_b for every sequence when host copies are given (use the
  * chunked entry point otherwise).
  * Limits (PDD_ERR_UNSUPPORTED beyond them; the kernels address with 32-bit byte
@@ -315,10 +322,12 @@ pdd_status pdd_pack_mask(const uint8_t *mask, int32_t n_rows, int32_t batch, int
                          uint8_t *out_bits, pdd_stream stream);
 
 /*
- * Bytes of DEVICE scratch `which_call` needs for this descriptor.  Never grows
+ * Bytes of DEVICE scratch `which_call` can use for this descriptor (0 when it
+ * has no use for any).  At most 8 * n_kv_heads * total_k * 4 bytes; never grows
  * with Nq*Nk: the attention weights are not materialised (Section 3.2
- * "Preliminaries").  For PDD_CALL_SELECT_TOPK only batch, n_kv_heads,
- * total_k and max_seqlen_k of the descriptor are read.
+ * "Preliminaries").  The figure depends on the descriptor and on the number of
+ * compute units of the current device only.  A call that is given less runs
+ * without scratch (see pdd_prefill_attn).
  */
 size_t pdd_workspace_bytes(const pdd_attn_desc *desc, int which_call);
 

@@ -33,6 +33,12 @@ struct ImpParams {
     int32_t B, Hq, Hkv, G, total_q, total_k, n_ktiles;
     int32_t window;    // < 0: every query is a window query
     float scale_log2;  // softmax scale * log2(e)
+    // Row split: the window rows of a workgroup's keys are divided over n_split workgroups; with
+    // n_split > 1 workgroup r writes its partial column sums to part[r][Hkv][total_k] (every
+    // element of a sequence, zeros included) and importance_reduce_kernel adds them in the
+    // fixed order r = 0, 1, ...
+    int32_t n_split;
+    float *part;
 };
 
 constexpr int kImpWaves = 4;
@@ -72,7 +78,8 @@ void importance_kernel(const ImpParams p)
     int bid = blockIdx.x;
     const int g = bid % p.Hkv;  bid /= p.Hkv;
     const int b = bid % p.B;    bid /= p.B;
-    const int kt = bid;
+    const int kt = bid % p.n_ktiles;
+    const int split = bid / p.n_ktiles;
 
     const int qs = min(p.cu_q[b], p.total_q), qe = min(p.cu_q[b + 1], p.total_q);
     const int ks = min(p.cu_k[b], p.total_k), ke = min(p.cu_k[b + 1], p.total_k);
@@ -106,7 +113,11 @@ void importance_kernel(const ImpParams p)
         // before key j_wg0 - delta see none of this workgroup's keys and are skipped
         const int n_rb = (W + 31) / 32;
         const int rb_first = min(n_rb, max(0, (j_wg0 - delta - iw0) / 32));
-        const int n_items = p.G * (n_rb - rb_first);
+        const int n_items_all = p.G * (n_rb - rb_first);
+        // this workgroup's share of the row blocks: items [item0, item0 + n_items)
+        const int per_split = (n_items_all + p.n_split - 1) / p.n_split;
+        const int item0 = min(split * per_split, n_items_all);
+        const int n_items = min(per_split, n_items_all - item0);
 
         // Q rows of this sequence, all heads: buffer descriptor spanning the whole sequence
         const uint16_t *qbase = p.q + (int64_t)qs * p.q_st;
@@ -127,7 +138,8 @@ void importance_kernel(const ImpParams p)
             qrow_l[ci] = r;
             qvoff[ci] = (uint32_t)c * 16u;
         }
-        auto issue_item = [&](int item, int buf) {
+        auto issue_item = [&](int item_local, int buf) {
+            const int item = item0 + item_local;
             const int hg = item / (n_rb - rb_first), rb = rb_first + item % (n_rb - rb_first);
             const int h = g * p.G + hg;
             const int i0 = iw0 + 32 * rb;
@@ -162,7 +174,7 @@ void importance_kernel(const ImpParams p)
             else wait_vmcnt<0>();
             __syncthreads();     // every wave's part of the block has landed; the buffer refilled below is free
             if (item + kImpAhead < n_items) issue_item(item + kImpAhead, (item + kImpAhead) & (kImpBufs - 1));
-            const int rb = rb_first + item % (n_rb - rb_first);
+            const int rb = rb_first + (item0 + item) % (n_rb - rb_first);
             const int i0 = iw0 + 32 * rb;
             const int i_last = min(i0 + 31, nq - 1);
             if (jw0 <= i_last + delta && jw0 < nk) {       // some row of the block sees some key of the wave
@@ -203,11 +215,22 @@ void importance_kernel(const ImpParams p)
 #pragma unroll
     for (int kg = 0; kg < 2; ++kg) {
         const float tot = colsum[kg] + xchg_half(colsum[kg]);
-        if (hh == 0 && jkey[kg] < nk) p.imp[(int64_t)g * p.total_k + ks + jkey[kg]] = tot;
+        float *dst = p.n_split > 1 ? p.part + (int64_t)split * p.Hkv * p.total_k : p.imp;
+        if (hh == 0 && jkey[kg] < nk) dst[(int64_t)g * p.total_k + ks + jkey[kg]] = tot;
     }
 #else
     (void)p;
 #endif
+}
+
+// imp[x] = part[0][x] + part[1][x] + ... in that order, x over Hkv * total_k elements
+__global__ __launch_bounds__(256) void importance_reduce_kernel(const float *part, float *imp, int64_t n, int n_split)
+{
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (x >= n) return;
+    float acc = part[x];
+    for (int r = 1; r < n_split; ++r) acc += part[(int64_t)r * n + x];
+    imp[x] = acc;
 }
 
 }  // namespace pdd

@@ -34,7 +34,15 @@ class DeviceWorkload:
         self.total_keep = int(wl.cu_keep[-1])
         self.idx = torch.empty((wl.n_kv_heads, self.total_keep), dtype=torch.int32, device="cuda")
         self.mask = torch.empty((wl.n_kv_heads, wl.total_k), dtype=torch.uint8, device="cuda")
-        self.workspace = None
+        # scratch for the calls that can use one (the importance step divides its window rows over
+        # several workgroups when it gets room for their partial sums)
+        desc, keep = pdd.make_desc(self.q, self.k, self.v, self.o, self.cu_q, self.cu_k, self.max_q, self.max_k,
+                                   wl.scale, wl.window)
+        call = pdd.CALL_PREFILL_ATTN_CHUNKED if wl.chunked else pdd.CALL_PREFILL_ATTN
+        self.workspace_bytes = pdd.workspace_bytes(desc, call) if wl.total_k else 0
+        self.workspace = (torch.empty(self.workspace_bytes, dtype=torch.uint8, device="cuda")
+                          if self.workspace_bytes else None)
+        del keep
 
     def poison(self):
         """Fill the outputs with junk so that an unwritten element shows."""
@@ -44,25 +52,26 @@ class DeviceWorkload:
         self.idx.fill_(-7)
         self.mask.fill_(9)
 
-    def attn(self, with_importance=True, host_cu=True):
+    def attn(self, with_importance=True, host_cu=True, use_workspace=True):
         wl = self.wl
         hq = wl.cu_seqlens_q if host_cu else None
         hk = wl.cu_seqlens_k if host_cu else None
+        ws = self.workspace if use_workspace else None
         if wl.chunked:
             pdd.prefill_attn_chunked(self.q, self.k, self.v, self.o, self.lse,
                                      self.imp if with_importance else None, self.cu_q, self.cu_k,
-                                     self.max_q, self.max_k, wl.scale, hq, hk)
+                                     self.max_q, self.max_k, wl.scale, hq, hk, workspace=ws)
         else:
             pdd.prefill_attn(self.q, self.k, self.v, self.o, self.lse,
                              self.imp if with_importance else None, self.cu_q, self.cu_k,
                              self.max_q, self.max_k, wl.scale,
-                             wl.window if with_importance else 0, hq, hk)
+                             wl.window if with_importance else 0, hq, hk, workspace=ws)
 
     def select(self, scores=None):
         wl = self.wl
         pdd.select_topk(self.imp if scores is None else scores, self.cu_k, self.max_k,
                         self.k_keep, self.cu_keep, self.total_keep, self.idx, self.mask,
-                        self.cand_b, self.cand_e, wl.cu_seqlens_k, workspace=self.workspace)
+                        self.cand_b, self.cand_e, wl.cu_seqlens_k)
 
     def step(self):
         """One pass of the whole hot path."""

@@ -219,3 +219,22 @@ def test_pack_mask_layout_matches_the_oracle_layout():
     assert np.array_equal(got, want) and total == int(want[-1]) == sum((int(n) + 7) // 8 for n in np.diff(cu))
     with pytest.raises(pdd.PddError):
         pdd.pack_mask_layout(np.array([0, 5, 3], dtype=np.int32))
+
+
+def test_workspace_bytes_host_only():
+    """The scratch size is a pure function of the descriptor (and the device's compute-unit count,
+    256 when no device is visible): 0 where the importance step is not divided, otherwise a whole
+    number of [n_kv_heads, total_k] fp32 planes, at most 8."""
+    lib = pdd.load_library()
+    d = good_desc()                                     # 64 tokens, window 8: a single row block
+    assert lib.pdd_workspace_bytes(ctypes.byref(d), 0) == 0
+    d = good_desc()                                     # chunked catch-up shape: 4 x (8192 + 256) keys, 64/8 heads
+    d.batch, d.n_q_heads, d.n_kv_heads = 4, 64, 8
+    d.total_q, d.max_seqlen_q, d.total_k, d.max_seqlen_k = 1024, 256, 4 * 8448, 8448
+    plane = 8 * 4 * 8448 * 4
+    for call in (1, 2):
+        d.window = -1
+        n = lib.pdd_workspace_bytes(ctypes.byref(d), call)
+        assert n > 0 and n % plane == 0 and n // plane <= 8
+    assert lib.pdd_workspace_bytes(ctypes.byref(d), 3) == 0          # the selection uses none
+    assert lib.pdd_workspace_bytes(None, 0) == 0

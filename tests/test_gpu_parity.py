@@ -144,9 +144,15 @@ def test_standalone_importance_equals_fused_and_is_deterministic():
     O1, l1, i1, x1, m1 = dev.results()
     imp2 = torch.full_like(dev.imp, float("nan"))
     pdd.token_importance(dev.q, dev.k, dev.lse, imp2, dev.cu_q, dev.cu_k, dev.max_q, dev.max_k,
-                         wl.scale, wl.window, wl.cu_seqlens_q, wl.cu_seqlens_k)
+                         wl.scale, wl.window, wl.cu_seqlens_q, wl.cu_seqlens_k, workspace=dev.workspace)
     torch.cuda.synchronize()
     assert np.array_equal(imp2.cpu().numpy(), dev.imp.cpu().numpy())
+    # without scratch the single-pass form runs: same values up to the order of the fp32 additions
+    imp3 = torch.full_like(dev.imp, float("nan"))
+    pdd.token_importance(dev.q, dev.k, dev.lse, imp3, dev.cu_q, dev.cu_k, dev.max_q, dev.max_k,
+                         wl.scale, wl.window, wl.cu_seqlens_q, wl.cu_seqlens_k)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(imp3.cpu().numpy(), dev.imp.cpu().numpy(), rtol=1e-5, atol=1e-12)
     dev.poison()
     dev.step()
     O2, l2, i2, x2, m2 = dev.results()
@@ -157,6 +163,28 @@ def test_standalone_importance_equals_fused_and_is_deterministic():
     dev.attn(with_importance=False)
     torch.cuda.synchronize()
     assert (dev.imp == -5.0).all()
+
+
+@pytest.mark.parametrize("name", ["c5", "chunk-ragged"])
+def test_importance_with_and_without_scratch(name):
+    """The importance step with its window rows divided over several workgroups (partial sums in
+    the caller's scratch, added in a fixed order) and as a single pass without scratch: both
+    against the oracle."""
+    if name == "c5":
+        wl = W.make_workload(name)
+    else:       # ragged chunks with 16 query heads per KV head, long enough for the split to pay
+        wl = W.make_custom("t", [200, 256, 77, 256], [200 + 9000, 256 + 7000, 77 + 8000, 256 + 8100], 32, 2, 128, 0,
+                           "1/4", seed=41, chunked=True)
+    dev = DeviceWorkload(wl)
+    assert dev.workspace_bytes > 0          # these shapes are split
+    oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, -1 if wl.chunked else wl.window)
+    for use_ws in (True, False):
+        dev.poison()
+        if dev.workspace is not None:
+            dev.workspace.fill_(0xFF)       # NaN patterns: a partial sum that is not overwritten shows
+        dev.attn(True, use_workspace=use_ws)
+        torch.cuda.synchronize()
+        rel_close(dev.imp.cpu().numpy().astype(np.float64), oI, f"{name} importance, scratch={use_ws}")
 
 
 @pytest.mark.parametrize("name", ["c5", "c3", "c4"])
