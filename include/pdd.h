@@ -142,6 +142,24 @@ pdd_status pdd_prefill_attn_chunked(const pdd_attn_desc *desc, const void *q_chu
                                     pdd_stream stream);
 
 /*
+ * pdd_prefill_attn_chunked for callers that cannot allocate device memory (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): same arguments without the workspace, same results bit for bit as
+ * pdd_prefill_attn_chunked called with a workspace of pdd_workspace_bytes(desc,
+ * PDD_CALL_PREFILL_ATTN_CHUNKED) bytes.  The scratch is a fixed 4 MiB array
+ * inside the library's device image (one copy per GPU, held until the process
+ * ends); the call allocates and frees nothing.  A shape whose scratch would
+ * exceed 4 MiB is rejected with PDD_ERR_WORKSPACE and nothing is enqueued.
+ * All calls on one GPU share that array: calls that overlap in time on the same
+ * GPU (different streams or threads) race on it and must be serialised by the
+ * caller.  Nothing in it has to be cleared between calls (every partial sum a
+ * call reads it has written itself).
+ */
+pdd_status pdd_prefill_attn_chunked_noalloc(const pdd_attn_desc *desc, const void *q_chunk,
+                                            const void *k_all, const void *v_all, void *o,
+                                            float *lse, float *importance, pdd_stream stream);
+
+/*
  * Token importance alone (Section 3.2 "Prompt Refiner"), from log-sum-exp
  * values computed earlier (e.g. by pdd_prefill_attn with importance = NULL):
  * same definition and same result as the fused output.  desc->window < 0

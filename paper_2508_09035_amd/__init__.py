@@ -13,6 +13,7 @@ from .binding import (
     set_option,
     prefill_attn,
     prefill_attn_chunked,
+    prefill_attn_chunked_noalloc,
     token_importance,
     select_topk,
     select_topk_pooled,
@@ -30,10 +31,14 @@ from .binding import (
     AttnDesc,
     make_desc,
     OPT_ATTN_WAVES,
+    CALL_PREFILL_ATTN,
+    CALL_PREFILL_ATTN_CHUNKED,
+    CALL_TOKEN_IMPORTANCE,
+    CALL_SELECT_TOPK,
 )
 
 __all__ = [
     "PddError", "library_path", "load_library", "version", "set_option", "prefill_attn",
-    "prefill_attn_chunked", "token_importance", "select_topk", "select_topk_pooled", "POOL_NONE", "POOL_MAX", "POOL_AVG", "select_sentences", "SENT_SUM", "SENT_MEAN", "pack_mask", "pack_mask_layout", "aggregate_scores", "choose_r_L", "workspace_bytes", "AttnDesc",
+    "prefill_attn_chunked", "prefill_attn_chunked_noalloc", "token_importance", "select_topk", "select_topk_pooled", "POOL_NONE", "POOL_MAX", "POOL_AVG", "select_sentences", "SENT_SUM", "SENT_MEAN", "pack_mask", "pack_mask_layout", "aggregate_scores", "choose_r_L", "workspace_bytes", "AttnDesc",
     "make_desc", "OPT_ATTN_WAVES",
 ]

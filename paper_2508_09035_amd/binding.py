@@ -63,6 +63,8 @@ def load_library():
     lib.pdd_prefill_attn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.pdd_prefill_attn_chunked.restype = ctypes.c_int
     lib.pdd_prefill_attn_chunked.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.pdd_prefill_attn_chunked_noalloc.restype = ctypes.c_int
+    lib.pdd_prefill_attn_chunked_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
     lib.pdd_token_importance.restype = ctypes.c_int
     lib.pdd_token_importance.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
     lib.pdd_select_topk.restype = ctypes.c_int
@@ -185,6 +187,19 @@ def prefill_attn_chunked(q_chunk, k_all, v_all, o, lse, importance, cu_seqlens_q
         ctypes.byref(desc), _ptr(q_chunk), _ptr(k_all), _ptr(v_all), _ptr(o), _ptr(lse),
         _ptr(importance), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+    del keep
+
+
+def prefill_attn_chunked_noalloc(q_chunk, k_all, v_all, o, lse, importance, cu_seqlens_q, cu_seqlens_k,
+                                 max_seqlen_q, max_seqlen_k, softmax_scale=0.0, cu_seqlens_q_host=None,
+                                 cu_seqlens_k_host=None):
+    """pdd_prefill_attn_chunked_noalloc: the chunked call on the library's built-in scratch."""
+    _check_tensors(q_chunk, k_all, v_all, o, lse, importance)
+    desc, keep = make_desc(q_chunk, k_all, v_all, o, cu_seqlens_q, cu_seqlens_k, max_seqlen_q,
+                           max_seqlen_k, softmax_scale, 0, cu_seqlens_q_host, cu_seqlens_k_host)
+    _check(load_library().pdd_prefill_attn_chunked_noalloc(
+        ctypes.byref(desc), _ptr(q_chunk), _ptr(k_all), _ptr(v_all), _ptr(o), _ptr(lse),
+        _ptr(importance), _stream()))
     del keep
 
 

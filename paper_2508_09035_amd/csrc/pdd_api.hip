@@ -19,6 +19,12 @@
 #include "aggregate.hpp"
 #include <mutex>
 
+// Scratch of the allocation-free entry point: one copy per GPU the library runs on, held until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the address
+// that kernels and memory calls use is the one that call returns for the current device.
+#define PDD_STATIC_SCRATCH_BYTES (4u << 20)
+static __device__ __align__(256) unsigned char scratch[PDD_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -271,6 +277,28 @@ pdd_status launch_importance(const pdd_attn_desc *d, const void *q, const void *
     return PDD_OK;
 }
 
+// Device address of this GPU's copy of `scratch`, looked up once per device.
+pdd_status static_scratch(void **out)
+{
+    static void *ptr[64];
+    static bool known[64];
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(PDD_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= 64) return fail(PDD_ERR_UNSUPPORTED, "device ordinal %d beyond 63", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!known[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(PDD_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        ptr[dev] = p;
+        known[dev] = true;
+    }
+    *out = ptr[dev];
+    return PDD_OK;
+}
+
 pdd_status check_ptrs(const void *q, const void *k, const void *v, const void *o, const void *lse)
 {
     if (!q || !k || !v || !o || !lse) return fail(PDD_ERR_INVALID_ARG, "NULL tensor pointer");
@@ -345,6 +373,24 @@ pdd_status pdd_prefill_attn_chunked(const pdd_attn_desc *desc, const void *q_chu
         return launch_importance(desc, q_chunk, k_all, lse, importance, -1, workspace, workspace_bytes,
                                  (hipStream_t)stream);
     return PDD_OK;
+}
+
+pdd_status pdd_prefill_attn_chunked_noalloc(const pdd_attn_desc *desc, const void *q_chunk, const void *k_all,
+                                            const void *v_all, void *o, float *lse, float *importance,
+                                            pdd_stream stream)
+{
+    pdd_status s = check_desc(desc, MODE_CHUNKED);
+    if (s) return s;
+    const size_t need = importance ? importance_workspace(desc, -1) : 0;
+    if (need > PDD_STATIC_SCRATCH_BYTES)
+        return fail(PDD_ERR_WORKSPACE, "this shape wants %zu bytes of scratch, the built-in scratch holds %u "
+                    "(use pdd_prefill_attn_chunked with a workspace)", need, (unsigned)PDD_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if (need > 0) {
+        s = static_scratch(&ws);
+        if (s) return s;
+    }
+    return pdd_prefill_attn_chunked(desc, q_chunk, k_all, v_all, o, lse, importance, ws, need, stream);
 }
 
 pdd_status pdd_token_importance(const pdd_attn_desc *desc, const void *q, const void *k, const float *lse,

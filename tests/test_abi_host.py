@@ -238,3 +238,21 @@ def test_workspace_bytes_host_only():
         assert n > 0 and n % plane == 0 and n // plane <= 8
     assert lib.pdd_workspace_bytes(ctypes.byref(d), 3) == 0          # the selection uses none
     assert lib.pdd_workspace_bytes(None, 0) == 0
+
+
+def test_noalloc_rejects_shapes_beyond_its_scratch():
+    """The allocation-free chunked entry point refuses, on the host, a shape whose scratch
+    would not fit its built-in 4 MiB array: nothing is launched."""
+    d = AttnDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = 4, 128, 8, 128     # 16 query heads per KV head, chunks of 1024
+    d.total_q, d.max_seqlen_q, d.total_k, d.max_seqlen_k = 4 * 1024, 1024, 4 * 8448, 8448
+    d.cu_seqlens_q = d.cu_seqlens_k = 0x1000          # never followed: validation fails first
+    for f in ("q", "k", "v", "o"):
+        heads = 128 if f in "qo" else 8
+        setattr(d, f + "_stride_tok", heads * 128)
+        setattr(d, f + "_stride_head", 128)
+    lib = pdd.load_library()
+    assert lib.pdd_workspace_bytes(ctypes.byref(d), pdd.CALL_PREFILL_ATTN_CHUNKED) > (4 << 20)
+    rc = lib.pdd_prefill_attn_chunked_noalloc(ctypes.byref(d), 0x10000, 0x20000, 0x30000, 0x40000, 0x50000,
+                                              0x60000, None)
+    assert rc == -3 and "scratch" in lib.pdd_last_error().decode()
