@@ -156,7 +156,11 @@ void attn_fwd_d128_kernel(const AttnParams p)
     // num_records reduced by the same amount, so that the range check still ends at the sequence's
     // last row and the per-lane offsets stay constant.
     auto tile_rsrc = [&](const uint16_t *base, uint32_t span, uint32_t so) {
-        return make_rsrc((const uint8_t *)base + so, span > so ? span - so : 0u);
+        // span - min(so, span) on the scalar unit (the compiler turns the C form into a saturating
+        // subtract, which exists only on the vector unit and then needs a readfirstlane)
+        uint32_t left;
+        asm("s_min_u32 %0, %1, %2\n\ts_sub_u32 %0, %2, %0" : "=&s"(left) : "s"(so), "s"(span) : "scc");
+        return make_rsrc((const uint8_t *)base + so, left);
     };
     auto issue_k = [&](int tile, int buf) {
         const i32x4 rs = tile_rsrc(kbase, k_span, (uint32_t)tile * kBN * k_row_bytes);
@@ -203,6 +207,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
     const float c2 = p.scale_log2;
     const float lazy = kLazyLog2 / c2;         // the same distance in units of the raw scores
     float neg_mc = 0.f;                        // -m_run * c2 (0 while m_run is -inf)
+    float m_thr = -INFINITY;                   // m_run + lazy: a row max above it renews the reference
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // S^T of the 32-key block at byte offset `koff` of the K buffers
@@ -235,6 +240,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
             for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
         m_run = m_new;
         neg_mc = (m_new == -INFINITY) ? 0.f : -m_new * c2;
+        m_thr = m_new + lazy;
     };
 
     auto exp_block = [&](f32x16 &s) {
@@ -296,14 +302,8 @@ void attn_fwd_d128_kernel(const AttnParams p)
     };
     // The wave runs at raised issue priority while it has the exponentials to do and at normal
     // priority during its PV MFMAs (measured: 1 % on the 32k prompt, 3 % on constant inputs).
-    auto premul = [&](f32x16 &s, float m) {
-        const float nm = -m * c2;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[e] = fmaf(s[e], c2, nm);
-    };
-    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, float &m_cand, uint32_t k_next2, uint32_t v_cur) {
+    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, uint32_t k_next2, uint32_t v_cur) {
         __builtin_amdgcn_s_setprio(1);
-        if (__any(m_cand > m_run)) rescale(m_cand);
         bf16x8 vf[2][NDB];
 #pragma unroll
         for (int st = 0; st < 2; ++st)
@@ -335,34 +335,37 @@ void attn_fwd_d128_kernel(const AttnParams p)
         // below 2^kLazyLog2, far inside the range of fp32 sums and bf16 operands).  O and the
         // row sums are therefore rescaled a few times per row instead of whenever a max moves.
         const float m_true = row_max(nxt);
-        m_cand = m_true > m_run + lazy ? m_true : m_run;
+        // rare, wave-uniform: O and the row sums (which by now include the current block) move to
+        // the new reference; the multiplications wait for the PV MFMAs above
+        if (__any(m_true > m_thr)) rescale(m_true > m_thr ? m_true : m_run);
         // The scale-and-subtract of the next block is done here, in the phase whose VALU is
-        // otherwise idle, against the reference the next phase 1 will adopt (m_cand >= m_run, and
-        // the rescale at the start of that phase sets m_run = m_cand in the lanes where it moved).
-        premul(nxt, m_cand);
+        // otherwise idle.
+#pragma unroll
+        for (int e = 0; e < 16; ++e) nxt[e] = fmaf(nxt[e], c2, neg_mc);
     };
-    auto hot_tile = [&](auto par_c, const int it, float &m_cand) {
+    auto hot_tile = [&](auto par_c, const int it) {
         constexpr int PAR = decltype(par_c)::value;
         constexpr int P1 = (PAR + 1) % 3, P2 = (PAR + 2) % 3;
         issue_v(it + 1, P1);
         if (it + 2 < n_tiles) issue_k(it + 2, P2);
-        hot_half(sA, sB, m_cand, P1 * kTileBytes, PAR * kTileBytes);
-        hot_half(sB, sA, m_cand, P1 * kTileBytes + 32 * 256, PAR * kTileBytes + 2 * 4096);
+        hot_half(sA, sB, P1 * kTileBytes, PAR * kTileBytes);
+        hot_half(sB, sA, P1 * kTileBytes + 32 * 256, PAR * kTileBytes + 2 * 4096);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };
     int it = 0;
     if (n_hot > 0) {
-        float m_cand = row_max(sA);
-        premul(sA, m_cand);
+        rescale(row_max(sA));                       // the first block sets every row's reference
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sA[e] = fmaf(sA[e], c2, neg_mc);
         load_kf(32 * 256);
         for (; it + 3 <= n_hot; it += 3) {          // unrolled over the three LDS buffers
-            hot_tile(std::integral_constant<int, 0>{}, it, m_cand);
-            hot_tile(std::integral_constant<int, 1>{}, it + 1, m_cand);
-            hot_tile(std::integral_constant<int, 2>{}, it + 2, m_cand);
+            hot_tile(std::integral_constant<int, 0>{}, it);
+            hot_tile(std::integral_constant<int, 1>{}, it + 1);
+            hot_tile(std::integral_constant<int, 2>{}, it + 2);
         }
-        if (it < n_hot) { hot_tile(std::integral_constant<int, 0>{}, it, m_cand); ++it; }
-        if (it < n_hot) { hot_tile(std::integral_constant<int, 1>{}, it, m_cand); ++it; }
+        if (it < n_hot) { hot_tile(std::integral_constant<int, 0>{}, it); ++it; }
+        if (it < n_hot) { hot_tile(std::integral_constant<int, 1>{}, it); ++it; }
         // the hot loop leaves sA scaled and shifted; the generic loop wants the raw scores of its
         // first block (one extra QK block per workgroup)
         qk_block((uint32_t)(it % 3) * kTileBytes, sA);
