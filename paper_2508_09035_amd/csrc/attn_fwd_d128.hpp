@@ -28,7 +28,7 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 constexpr int kTileBytes = kBN * 256;   // one K or V tile in LDS
 constexpr int kAttn128Bufs = 3;          // K and V tiles are triple buffered
 constexpr int kAttn128Smem = 2 * kAttn128Bufs * kTileBytes;
-constexpr float kLazyLog2 = 8.0f;        // a row's softmax reference may lag its running max by up to 2^8
+constexpr float kLazyLog2 = 8.0f;        // a row's softmax reference may lag its running max by a factor 2^8
 
 __device__ __forceinline__ int swz16(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
@@ -73,15 +73,6 @@ __device__ __forceinline__ bf16x8 lds_read_tr8(uint32_t lo, uint32_t hi)
     const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(uintptr_t)hi);
     const s16x8 c = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, c);
-}
-
-// max(m, x of this lane, x of the lane 32 positions away): after the swap of (x, x) the first
-// result holds the lower half's values in both halves and the second the upper half's
-__device__ __forceinline__ float max_with_other_half(float m, float x)
-{
-    const uint32_t u = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return max3(m, __uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 template <int NWAVES>
@@ -202,12 +193,17 @@ void attn_fwd_d128_kernel(const AttnParams p)
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
-    float m_run = -INFINITY;
+    // Online-softmax state of this lane's query, kept in the log2 domain: every score enters as
+    //   t = s * c2 + ref      (c2 = softmax scale * log2 e, ref = minus the row's reference exponent)
+    // and contributes 2^t.  The reference only has to keep 2^t in range, it need not be the
+    // running max: it is set by the first block that holds a visible key and renewed when a
+    // block's largest t exceeds kLazyLog2 (probabilities relative to it stay below 2^kLazyLog2,
+    // far inside the range of fp32 sums and bf16 operands), so O and the row sums are rescaled a
+    // few times per row instead of whenever a max moves.
     float l_part[4] = {0.f, 0.f, 0.f, 0.f};   // four interleaved partial row sums (short add chains)
     const float c2 = p.scale_log2;
-    const float lazy = kLazyLog2 / c2;         // the same distance in units of the raw scores
-    float neg_mc = 0.f;                        // -m_run * c2 (0 while m_run is -inf)
-    float m_thr = -INFINITY;                   // m_run + lazy: a row max above it renews the reference
+    float ref = 0.f;                           // 0 until the row has a reference
+    float thr = -INFINITY;                     // a block max above it renews the reference: -inf, then kLazyLog2
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // S^T of the 32-key block at byte offset `koff` of the K buffers
@@ -220,33 +216,49 @@ void attn_fwd_d128_kernel(const AttnParams p)
         }
     };
 
-    // short dependency chains: a 3-level tree of v_max3 instead of one serial chain
-    // max(m_run, row max of s): the query's keys are spread over this lane and lane ^ 32
+    // t = s * c2 + ref in place
+    auto to_log2 = [&](f32x16 &s) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[e] = fmaf(s[e], c2, ref);
+    };
+
+    // largest entry of the query's row in this block; its keys are spread over this lane and
+    // lane ^ 32.  Short dependency chains: a 3-level tree of v_max3 instead of one serial chain.
     auto row_max = [&](const f32x16 &s) {
         const float t0 = max3(s[0], s[1], s[2]), t1 = max3(s[4], s[5], s[6]);
         const float t2 = max3(s[8], s[9], s[10]), t3 = max3(s[12], s[13], s[14]);
         const float u0 = max3(t0, t1, s[3]), u1 = max3(t2, t3, s[7]);
         const float tmax = max3(max3(u0, u1, s[11]), s[15], s[15]);
-        return max_with_other_half(m_run, tmax);
+        const uint32_t u = __float_as_uint(tmax);
+        const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
     };
 
-    auto rescale = [&](float m_new) {
-        const float alpha = (m_run == -INFINITY) ? 0.f : fast_exp2((m_run - m_new) * c2);
+    // Rare and wave-uniform: the rows whose block max t_max exceeds their threshold take it as
+    // their new reference; O, the row sums and the block `blk` (already in the log2 domain) move
+    // with it.  Rows without a reference (thr = -inf, nothing accumulated yet) get their first
+    // one the same way; a block in which a row sees no key (t_max = -inf) changes nothing.
+    auto renew = [&](float t_max, f32x16 &blk) {
+        const bool up = t_max > thr;
+        const float shift = up ? t_max : 0.f;
+        const float alpha = fast_exp2(-shift);
 #pragma unroll
         for (int i = 0; i < 4; ++i) l_part[i] *= alpha;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-        m_run = m_new;
-        neg_mc = (m_new == -INFINITY) ? 0.f : -m_new * c2;
-        m_thr = m_new + lazy;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) blk[e] -= shift;
+        ref -= shift;
+        thr = up ? kLazyLog2 : thr;
     };
 
+    // a block in the log2 domain -> probabilities relative to the reference, added to the row sums
     auto exp_block = [&](f32x16 &s) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            s[e] = fast_exp2(fmaf(s[e], c2, neg_mc));
+            s[e] = fast_exp2(s[e]);
             l_part[e & 3] += s[e];
         }
     };
@@ -289,11 +301,11 @@ void attn_fwd_d128_kernel(const AttnParams p)
     const int first_lim = m0 + delta;
     const int n_hot = max(0, min((first_lim + 1) / kBN, n_tiles - 1));   // tiles 0 .. n_hot-1
 
-    // `m_cand` carries max(m_run, row max of `cur`), computed one block earlier while the
-    // previous PV MFMAs were running, so that the exponentials never wait for a max.  LDS
-    // fragment reads are issued a phase ahead of the MFMAs that consume them: the V^T
-    // fragments of `cur` before the QK MFMAs of `nxt`, the K fragments of the block after
-    // `nxt` (`kf`) before the PV MFMAs of `cur`.
+    // The block `cur` arrives in the log2 domain (see above): the scale-and-shift and the row max
+    // of a block are done one phase before its exponentials, while the previous PV MFMAs run, so
+    // that the exponentials never wait for a max.  LDS fragment reads are issued a phase ahead of
+    // the MFMAs that consume them: the V^T fragments of `cur` before the QK MFMAs of `nxt`, the K
+    // fragments of the block after `nxt` (`kf`) before the PV MFMAs of `cur`.
     bf16x8 kf[NKK];
     auto load_kf = [&](uint32_t koff) {
         const uint8_t *kb = Ks + koff;
@@ -302,7 +314,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
     };
     // The wave runs at raised issue priority while it has the exponentials to do and at normal
     // priority during its PV MFMAs (measured: 1 % on the 32k prompt, 3 % on constant inputs).
-    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, uint32_t k_next2, uint32_t v_cur) {
+    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, uint32_t k_next2, uint32_t v_cur) __attribute__((always_inline)) {
         __builtin_amdgcn_s_setprio(1);
         bf16x8 vf[2][NDB];
 #pragma unroll
@@ -314,34 +326,52 @@ void attn_fwd_d128_kernel(const AttnParams p)
         for (int kk = 0; kk < NKK; ++kk)
             nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], kk == 0 ? zero16 : nxt, 0, 0, 0);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) cur[e] = fast_exp2(cur[e]);   // cur holds s * c2 - m * c2 (see below)
-        __builtin_amdgcn_s_setprio(0);
-        load_kf(k_next2);
+        for (int e = 0; e < 16; ++e) cur[e] = fast_exp2(cur[e]);   // cur is in the log2 domain
+        bf16x8 pb[2];
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
             f32x8 pf;
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[e] = cur[8 * st + e];
-            const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
+            pb[st] = __builtin_convertvector(pf, bf16x8);
+        }
+        // Issue order of this phase, pinned: after every QK MFMA two exponentials, two V^T
+        // fragment reads and one bf16 pack.  Left to itself the compiler bunches the exponentials
+        // behind the first MFMAs and the reads behind the middle ones, and the two waves of a SIMD
+        // then queue for the same unit (measured: 10 % fewer cycles on constant inputs, 2.5 % less
+        // time on the 32k prompt, where the clock gives way as the matrix pipe fills).
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // 2 transcendental
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // 2 DS reads
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);   // 1 VALU (a bf16 pack)
+        }
+        __builtin_amdgcn_s_setprio(0);
+        load_kf(k_next2);
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            const bf16x8 pbs = pb[st];
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pb, oacc[db], 0, 0, 0);
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pbs, oacc[db], 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) l_part[e & 3] += cur[e];      // row sums: also in this phase
-        // The reference m_run of the exponentials only has to keep them in range, it need not be the
-        // exact running max: a row adopts a new reference when its max has moved by more than
-        // kLazyLog2 binary orders of magnitude (probabilities relative to the reference then stay
-        // below 2^kLazyLog2, far inside the range of fp32 sums and bf16 operands).  O and the
-        // row sums are therefore rescaled a few times per row instead of whenever a max moves.
-        const float m_true = row_max(nxt);
-        // rare, wave-uniform: O and the row sums (which by now include the current block) move to
-        // the new reference; the multiplications wait for the PV MFMAs above
-        if (__any(m_true > m_thr)) rescale(m_true > m_thr ? m_true : m_run);
-        // The scale-and-subtract of the next block is done here, in the phase whose VALU is
-        // otherwise idle.
+        // The next block enters the log2 domain here, in the phase whose VALU is otherwise idle,
+        // against the present reference (nothing here depends on the check below, so all of it can
+        // be issued between the PV MFMAs).
+        to_log2(nxt);
+        const float t_max = row_max(nxt);
+        // same for this phase: after every PV MFMA one K fragment read and five of the additions,
+        // multiply-adds and max operations above
 #pragma unroll
-        for (int e = 0; e < 16; ++e) nxt[e] = fmaf(nxt[e], c2, neg_mc);
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);   // 5 VALU
+        }
+        if (__any(t_max > thr)) renew(t_max, nxt);
     };
     auto hot_tile = [&](auto par_c, const int it) {
         constexpr int PAR = decltype(par_c)::value;
@@ -355,9 +385,8 @@ void attn_fwd_d128_kernel(const AttnParams p)
     };
     int it = 0;
     if (n_hot > 0) {
-        rescale(row_max(sA));                       // the first block sets every row's reference
-#pragma unroll
-        for (int e = 0; e < 16; ++e) sA[e] = fmaf(sA[e], c2, neg_mc);
+        to_log2(sA);                                // the first block sets every row's reference
+        renew(row_max(sA), sA);
         load_kf(32 * 256);
         for (; it + 3 <= n_hot; it += 3) {          // unrolled over the three LDS buffers
             hot_tile(std::integral_constant<int, 0>{}, it);
@@ -385,8 +414,9 @@ void attn_fwd_d128_kernel(const AttnParams p)
                     if (j > lim) cur[e] = -INFINITY;
                 }
             }
-            const float m_new = row_max(cur);
-            if (__any(m_new > m_run)) rescale(m_new);
+            to_log2(cur);                         // masked entries stay -inf
+            const float t_max = row_max(cur);
+            if (__any(t_max > thr)) renew(t_max, cur);
             exp_block(cur);
             pv_block(v_cur, cur);
         }
@@ -420,7 +450,7 @@ void attn_fwd_d128_kernel(const AttnParams p)
         }
         if (hh == 0) {
             const float lse = l_tot > 0.f
-                ? (m_run * c2 + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f
+                ? (__builtin_amdgcn_logf(l_tot) - ref) * 0.6931471805599453f
                 : -INFINITY;
             p.lse[(int64_t)h * p.total_q + qs + qrow] = lse;
         }
