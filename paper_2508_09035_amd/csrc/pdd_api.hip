@@ -441,7 +441,19 @@ pdd_status pdd_select_topk_pooled(const float *scores, int32_t n_heads, int32_t 
     p.pooled_out = pooled_out;
     const dim3 grid((unsigned)batch, (unsigned)n_heads);
     hipStream_t st = (hipStream_t)stream;
-    if (max_seqlen_k <= 4 * pdd::kSelThreads)
+    // unpooled scores from 16-byte aligned tensors: four candidates per lane and step
+    const bool quads = p.pool_r == 0 && (reinterpret_cast<uintptr_t>(scores) & 15u) == 0 &&
+                       (reinterpret_cast<uintptr_t>(out_mask) & 3u) == 0;
+    const int span = max_seqlen_k;
+    if (quads && span <= 4 * pdd::kSelThreads)
+        hipLaunchKernelGGL(pdd::select_topk_quad_kernel<1>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    else if (quads && span <= 8 * pdd::kSelThreads)
+        hipLaunchKernelGGL(pdd::select_topk_quad_kernel<2>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    else if (quads && span <= 16 * pdd::kSelThreads)
+        hipLaunchKernelGGL(pdd::select_topk_quad_kernel<4>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    else if (quads && span <= 32 * pdd::kSelThreads)
+        hipLaunchKernelGGL(pdd::select_topk_quad_kernel<8>, grid, dim3(pdd::kSelThreads), 0, st, p);
+    else if (max_seqlen_k <= 4 * pdd::kSelThreads)
         launch_select_reg<4>(p, grid, st);
     else if (max_seqlen_k <= 8 * pdd::kSelThreads)
         launch_select_reg<8>(p, grid, st);

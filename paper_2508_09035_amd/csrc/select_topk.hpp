@@ -258,6 +258,287 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
 }
 
 // ---------------------------------------------------------------------------
+// Register-resident selection, four consecutive candidates per lane and step (unpooled scores
+// from a 16-byte aligned tensor).  Thread `tid` owns the quads q = i * 1024 + tid, i < QPT, of
+// the row's 16-byte aligned part (the up to three candidates before the first 16-byte boundary
+// sit one each in the first lanes of wave 0).  Against the one-candidate-per-lane kernel above: 16-byte loads, the mask written four bytes at a time, and a threshold
+// search that leaves the block-wide probes (each one costs a barrier) as soon as the keys still
+// in the bracket fit into one wave's registers; that wave finishes the bisection on its own.
+// ---------------------------------------------------------------------------
+constexpr int kSelWaveKeys = 2048;     // bracket size at which one wave takes over (32 keys per lane)
+
+// inclusive prefix sum over the 64 lanes of a wave (DPP row shifts and row broadcasts)
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
+{
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);   // row_shr:1
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);   // row_shr:2
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);   // row_shr:4
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);   // row_shr:8
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
+    return x;
+}
+
+template <int QPT>
+__global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const SelParams p)
+{
+    __shared__ uint32_t wred[2][kSelWaves];
+    __shared__ uint32_t wave_min[kSelWaves], wave_max[kSelWaves];
+    __shared__ uint32_t cnt[kSelWaves * QPT];          // per (i, wave): gt count | eq count << 16
+    __shared__ uint32_t cnt_wave_tot[kSelWaves];
+    __shared__ uint32_t fin_keys[kSelWaveKeys];
+    __shared__ uint32_t fin_T, fin_above, head_tot;
+
+    const int b = blockIdx.x, g = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ks = min(max(p.cu_k[b], 0), p.total_k);
+    const int ke = min(max(p.cu_k[b + 1], ks), p.total_k);
+    const int nk = ke - ks;
+    int c0 = p.cand_b ? p.cand_b[b] : 0;
+    int c1 = p.cand_e ? p.cand_e[b] : nk;
+    c0 = min(max(c0, 0), nk);
+    c1 = min(max(c1, c0), nk);
+    const int n = min(c1 - c0, 4 * kSelThreads * QPT);
+    // Candidates 0 .. nhead-1 (at most three) precede the first 16-byte boundary of the row; lanes
+    // 0 .. nhead-1 of wave 0 hold one each.  Candidate nhead + 4q + j is element j of quad q.
+    const int64_t elem0 = (int64_t)g * p.total_k + ks + c0;      // first candidate, in elements of `scores`
+    const int nhead = min((int)((4 - (elem0 & 3)) & 3), n);
+    const int nq_el = n - nhead;                                 // candidates inside quads
+    const int keep0 = min(max(p.cu_keep[b], 0), p.total_keep);
+    const int keep1 = min(max(p.cu_keep[b + 1], keep0), p.total_keep);
+    const int slots = keep1 - keep0;
+    const int kk = min(min(max(p.k_per[b], 0), n), slots);
+
+    const float *seq = p.scores + (int64_t)g * p.total_k + ks;
+    int32_t *out = p.out_idx + (int64_t)g * p.total_keep + keep0;
+    uint8_t *mrow = p.out_mask ? p.out_mask + (int64_t)g * p.total_k + ks : nullptr;
+
+    if (p.pooled_out) {
+        float *po = p.pooled_out + (int64_t)g * p.total_k + ks;
+        for (int x = tid; x < nk; x += kSelThreads) po[x] = seq[x];
+    }
+    if (mrow) {
+        for (int x = tid; x < c0; x += kSelThreads) mrow[x] = 0;
+        for (int x = c0 + n + tid; x < nk; x += kSelThreads) mrow[x] = 0;
+    }
+    for (int x = kk + tid; x < slots; x += kSelThreads) out[x] = -1;
+    if (kk == 0) {
+        if (mrow)
+            for (int x = c0 + tid; x < c0 + n; x += kSelThreads) mrow[x] = 0;
+        return;
+    }
+
+    // ---- keys into registers.  Slots outside the row hold key 0, which is below the key of
+    // every finite score.
+    const bool has_head = tid < nhead;
+    const uint32_t khead = has_head ? order_key(seq[c0 + tid]) : 0u;
+    const float *qbase = seq + c0 + nhead;                       // 16-byte aligned
+    uint32_t key[QPT][4];
+#pragma unroll
+    for (int i = 0; i < QPT; ++i) {
+        const int x0 = 4 * (i * kSelThreads + tid);              // index inside the quad part
+        float f[4] = {0.f, 0.f, 0.f, 0.f};
+        if (x0 + 3 < nq_el) {
+            const float4 t = *(const float4 *)(qbase + x0);
+            f[0] = t.x;  f[1] = t.y;  f[2] = t.z;  f[3] = t.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (x0 + j < nq_el) f[j] = qbase[x0 + j];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) key[i][j] = (x0 + j < nq_el) ? order_key(f[j]) : 0u;
+    }
+    uint32_t kmin = has_head ? khead : 0xffffffffu, kmax = khead;
+#pragma unroll
+    for (int i = 0; i < QPT; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool in = 4 * (i * kSelThreads + tid) + j < nq_el;
+            kmin = in ? min(kmin, key[i][j]) : kmin;
+            kmax = max(kmax, key[i][j]);
+        }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
+    }
+    if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
+
+    // ---- threshold search, block-wide part: bisection on the key value as in the kernel above,
+    // until at most kSelWaveKeys keys are left in the bracket [lo, hi]; every probed value is
+    // > lo >= kmin > 0, so empty slots never count.
+    uint32_t lo = kmin, hi = kmax;
+    uint32_t c_lo = (uint32_t)n, c_above = 0;
+    int par = 0;
+    while (lo < hi && c_lo - c_above > (uint32_t)kSelWaveKeys) {
+        const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+        uint32_t c = (uint32_t)__popcll(__ballot(khead >= mid));
+#pragma unroll
+        for (int i = 0; i < QPT; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c += (uint32_t)__popcll(__ballot(key[i][j] >= mid));
+        if (lane == 0) wred[par][wave] = c;
+        __syncthreads();
+        uint32_t tot = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) tot += wred[par][w];
+        par ^= 1;
+        if (tot >= (uint32_t)kk) { lo = mid; c_lo = tot; }
+        else { hi = mid - 1u; c_above = tot; }
+    }
+    if (lo < hi) {
+        // ---- the keys still inside [lo, hi] (at most kSelWaveKeys) go to LDS, in any order ...
+        // (lo >= kmin > 0: empty slots are outside the bracket)
+        uint32_t mine = (khead >= lo && khead <= hi) ? 1u : 0u;
+#pragma unroll
+        for (int i = 0; i < QPT; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mine += (key[i][j] >= lo && key[i][j] <= hi) ? 1u : 0u;
+        const uint32_t incl = wave_incl_scan(mine);
+        if (lane == 63) cnt_wave_tot[wave] = incl;
+        __syncthreads();
+        uint32_t pos = incl - mine;
+        for (int w = 0; w < wave; ++w) pos += cnt_wave_tot[w];
+        uint32_t m_tot = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) m_tot += cnt_wave_tot[w];
+        if (khead >= lo && khead <= hi) fin_keys[pos++] = khead;
+#pragma unroll
+        for (int i = 0; i < QPT; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (key[i][j] >= lo && key[i][j] <= hi) fin_keys[pos++] = key[i][j];
+        __syncthreads();
+        // ---- ... and one wave, KPL of them per lane, continues the bisection without barriers
+        // until at most kSelFinish keys are left, which it ranks directly: the r-th largest of
+        // the m_tot keys, r = kk - c_above
+        if (wave == 0) {
+            constexpr int KPL = kSelWaveKeys / 64;
+            uint32_t fk[KPL];
+#pragma unroll
+            for (int t = 0; t < KPL; ++t) fk[t] = (t * 64 + lane) < (int)m_tot ? fin_keys[t * 64 + lane] : 0u;
+            const uint32_t r = (uint32_t)kk - c_above;              // 1 <= r <= m_tot
+            uint32_t wlo = lo, whi = hi;
+            uint32_t w_ge = m_tot, above = 0;                       // count(key >= wlo), count(key > whi)
+            while (wlo < whi && w_ge - above > (uint32_t)kSelFinish) {
+                const uint32_t mid = wlo + ((whi - wlo + 1u) >> 1);
+                uint32_t c = 0;
+#pragma unroll
+                for (int t = 0; t < KPL; ++t) c += (uint32_t)__popcll(__ballot(fk[t] >= mid));
+                if (c >= r) { wlo = mid; w_ge = c; }
+                else { whi = mid - 1u; above = c; }
+            }
+            uint32_t T_w = wlo;
+            if (wlo < whi) {
+                // the keys inside [wlo, whi] (at most kSelFinish) in the first LDS slots, then the
+                // (r - above)-th largest of them by counting
+                const uint64_t lt_mask = (1ull << lane) - 1ull;
+                uint32_t m = 0;
+#pragma unroll
+                for (int t = 0; t < KPL; ++t) {
+                    const bool inb = fk[t] >= wlo && fk[t] <= whi;      // empty slots hold 0 < wlo
+                    const uint64_t bal = __ballot(inb);
+                    if (inb) fin_keys[m + __popcll(bal & lt_mask)] = fk[t];
+                    m += (uint32_t)__popcll(bal);
+                }
+                const uint32_t mine_k = lane < (int)m ? fin_keys[lane] : 0u;
+                uint32_t gt = 0, ge = 0;
+                for (uint32_t j = 0; j < m; ++j) {
+                    const uint32_t o = fin_keys[j];
+                    gt += o > mine_k ? 1u : 0u;
+                    ge += o >= mine_k ? 1u : 0u;
+                }
+                const uint32_t rr = r - above;                             // 1 <= rr <= m
+                const bool hit = lane < (int)m && gt < rr && rr <= ge;     // every hit lane holds the same key
+                const uint64_t hb = __ballot(hit);
+                const int src = hb ? (int)__builtin_ctzll(hb) : 0;
+                T_w = (uint32_t)__shfl((int)mine_k, src, 64);
+                above += (uint32_t)__shfl((int)gt, src, 64);
+            }
+            if (lane == 0) { fin_T = T_w; fin_above = c_above + above; }
+        }
+        __syncthreads();
+        lo = fin_T;
+        c_above = fin_above;
+    }
+    const uint32_t T = lo;
+    const int krem = kk - (int)c_above;     // ties at T to keep (>= 1), lowest index first
+
+    // ---- counts of keys > T and == T in index order: the head, then (i major, lane, j)
+    const uint32_t c_head = (has_head && khead > T ? 1u : 0u) | (has_head && khead == T ? 0x10000u : 0u);
+    uint32_t pre_head = 0;                  // wave 0: exclusive prefix over the head lanes
+    if (wave == 0) {
+        const uint32_t incl = wave_incl_scan(c_head);
+        pre_head = incl - c_head;
+        if (lane == 63) head_tot = incl;
+    }
+    uint32_t pre[QPT];                      // exclusive prefix inside the wave, packed gt | eq << 16
+#pragma unroll
+    for (int i = 0; i < QPT; ++i) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool in = 4 * (i * kSelThreads + tid) + j < nq_el;
+            c += (in && key[i][j] > T) ? 1u : 0u;
+            c += (in && key[i][j] == T) ? 0x10000u : 0u;
+        }
+        const uint32_t incl = wave_incl_scan(c);
+        pre[i] = incl - c;
+        if (lane == 63) cnt[i * kSelWaves + wave] = incl;
+    }
+    __syncthreads();
+    constexpr int NC = kSelWaves * QPT;                 // <= 128 entries
+    {
+        const uint32_t v = tid < NC ? cnt[tid] : 0u;
+        const uint32_t incl = wave_incl_scan(v);
+        if (lane == 63) cnt_wave_tot[wave] = incl;
+        __syncthreads();
+        uint32_t wave_off = head_tot;
+        for (int w = 0; w < wave; ++w) wave_off += cnt_wave_tot[w];
+        if (tid < NC) cnt[tid] = wave_off + incl - v;   // exclusive prefix over the head and (i, wave)
+        __syncthreads();
+    }
+
+    // ---- stable compaction
+    if (has_head) {
+        const int gt_before = (int)(pre_head & 0xffffu), eq_before = (int)(pre_head >> 16);
+        const bool sel = khead > T || (khead == T && eq_before < krem);
+        if (sel) out[gt_before + min(eq_before, krem)] = c0 + tid;
+        if (mrow) mrow[c0 + tid] = sel ? 1 : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < QPT; ++i) {
+        const int x0 = 4 * (i * kSelThreads + tid);
+        const uint32_t before = cnt[i * kSelWaves + wave] + pre[i];
+        int gt_before = (int)(before & 0xffffu), eq_before = (int)(before >> 16);
+        uint32_t mbytes = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool in = x0 + j < nq_el;
+            const bool is_gt = in && key[i][j] > T, is_eq = in && key[i][j] == T;
+            const bool sel = is_gt || (is_eq && eq_before < krem);
+            if (sel) out[gt_before + min(eq_before, krem)] = c0 + nhead + x0 + j;
+            gt_before += is_gt ? 1 : 0;
+            eq_before += is_eq ? 1 : 0;
+            mbytes |= sel ? (1u << (8 * j)) : 0u;
+        }
+        if (mrow && x0 < nq_el) {
+            uint8_t *mp = mrow + c0 + nhead + x0;                          // 4-byte aligned
+            if (x0 + 3 < nq_el) *(uint32_t *)mp = mbytes;
+            else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (x0 + j < nq_el) mp[j] = (uint8_t)((mbytes >> (8 * j)) & 1u);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Radix selection for rows longer than 32768 candidates (keys re-read from L2).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const SelParams p)
