@@ -286,6 +286,30 @@ def test_select_exact_in_every_register_variant(n):
     _select_case(s, lens, [n // 4, 1, 5], cand=([7, 0, 1], [n - 5, 1, n // 3 - 1]))
 
 
+@pytest.mark.parametrize("n", [1000, 6000, 12000, 32768])
+def test_select_unaligned_score_tensor(n):
+    """A score tensor that does not start on a 16-byte boundary takes the one-candidate-per-lane
+    kernel (4, 8, 16, 32 keys per thread at these lengths); same exactness."""
+    rng = np.random.default_rng(n + 1)
+    lens = [n, 77]
+    heads = 2
+    s = rng.integers(0, 300, size=(heads, sum(lens))).astype(np.float64) / 32.0
+    s[1] = rng.standard_normal(sum(lens))
+    wl = W.make_custom("t", lens, None, 1, 1, 64, 0, seed=0)
+    wl.n_kv_heads = heads
+    wl.k_keep = np.array([n // 7, 30], dtype=np.int32)
+    dev = DeviceWorkload(wl)
+    dev.poison()
+    flat = torch.zeros(heads * sum(lens) + 1, dtype=torch.float32, device="cuda")
+    view = flat[1:].view(heads, sum(lens))
+    view.copy_(torch.from_numpy(s.astype(np.float32)))
+    assert view.data_ptr() % 16 == 4
+    dev.select(scores=view)
+    torch.cuda.synchronize()
+    idx, mask = dev.idx.cpu().numpy(), dev.mask.cpu().numpy()
+    check_selection(s.astype(np.float32).astype(np.float64), idx, mask, wl, -1, "unaligned fp32")
+
+
 # ------------------------------------------------------ benchmark configurations
 def test_c2_llama_layer_full():
     wl = W.make_workload("c2")
