@@ -9,9 +9,8 @@
 //   varying   eight different A and B fragments taken from a caller-supplied
 //             buffer (random bf16 patterns) are cycled, so consecutive MFMAs
 //             see unrelated operands, as in a real contraction.
-// Lane 0 of every workgroup records the shader-clock counter and the
-// constant-rate wall clock before and after its loop, so that the host can
-// derive the clock the kernel ran at.
+// The loop is bound by the matrix pipe alone (32 cycles per MFMA and SIMD), so
+// cycles needed / duration bounds the clock the run had from below.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -25,7 +24,7 @@ constexpr int kFrags = 8;
 
 template <bool VARYING>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void mfma_probe_kernel(const uint16_t *operands, int iters, uint64_t *ticks, float *sink)
+void mfma_probe_kernel(const uint16_t *operands, int iters, float *sink)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     bf16x8 a[kFrags], b[kFrags];
@@ -46,8 +45,6 @@ void mfma_probe_kernel(const uint16_t *operands, int iters, uint64_t *ticks, flo
 #pragma unroll
         for (int e = 0; e < 16; ++e) c[r][e] = 0.f;
 
-    uint64_t t0 = 0, w0 = 0;
-    if (threadIdx.x == 0) { t0 = clock64(); w0 = wall_clock64(); }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < kFrags; ++i)
@@ -58,28 +55,15 @@ void mfma_probe_kernel(const uint16_t *operands, int iters, uint64_t *ticks, flo
     for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s += c[r][e];
-    if (threadIdx.x == 0) {
-        ticks[2 * blockIdx.x] = clock64() - t0;
-        ticks[2 * blockIdx.x + 1] = wall_clock64() - w0;
-    }
     sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = s;
 #else
-    (void)operands; (void)iters; (void)ticks; (void)sink;
+    (void)operands; (void)iters; (void)sink;
 #endif
 }
 
 }  // namespace
 
 extern "C" {
-
-// Rate of the constant-rate wall clock of the current device in kHz (0 on error).
-int pdd_probe_wall_clock_khz(void)
-{
-    int dev = 0, khz = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return 0;
-    return khz;
-}
 
 // Bytes of `operands` the varying mode reads (random bf16 patterns with finite values).
 int pdd_probe_operand_bytes(void) { return kThreads * 2 * kFrags * 16; }
@@ -92,18 +76,16 @@ double pdd_probe_mfma_flops(int blocks, int iters)
 
 // Enqueue one probe launch on `stream`.  All pointers are DEVICE memory owned by the
 // caller: operands (pdd_probe_operand_bytes() bytes, read only when varying != 0),
-// ticks uint64[2 * blocks] (per workgroup: shader-clock ticks, wall-clock ticks),
 // sink float[blocks * 512].  Returns 0, or the hipError_t of a failed launch.
-int pdd_probe_mfma(int varying, int blocks, int iters, const void *operands, void *ticks, void *sink,
-                   void *stream)
+int pdd_probe_mfma(int varying, int blocks, int iters, const void *operands, void *sink, void *stream)
 {
-    if (blocks < 1 || iters < 1 || !ticks || !sink || (varying && !operands)) return (int)hipErrorInvalidValue;
+    if (blocks < 1 || iters < 1 || !sink || (varying && !operands)) return (int)hipErrorInvalidValue;
     if (varying)
         hipLaunchKernelGGL(mfma_probe_kernel<true>, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream,
-                           (const uint16_t *)operands, iters, (uint64_t *)ticks, (float *)sink);
+                           (const uint16_t *)operands, iters, (float *)sink);
     else
         hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream,
-                           (const uint16_t *)operands, iters, (uint64_t *)ticks, (float *)sink);
+                           (const uint16_t *)operands, iters, (float *)sink);
     return (int)hipGetLastError();
 }
 
