@@ -40,6 +40,10 @@ struct AttnParams {
     int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh;
     int32_t B, Hq, Hkv, G, total_q, total_k, n_qtiles;
     float scale_log2;  // softmax scale * log2(e)
+    // Only read by kernels built with the importance sweep: partial column sums
+    // [G * n_qtiles][Hkv][total_k], slice hg * n_qtiles + t written by the workgroup of query
+    // head g * G + hg and query tile t (every key of its sequence, zeros included).
+    float *imp_part;
 };
 
 constexpr int kBN = 64;  // keys per LDS tile

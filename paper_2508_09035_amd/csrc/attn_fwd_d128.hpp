@@ -28,6 +28,9 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 constexpr int kTileBytes = kBN * 256;   // one K or V tile in LDS
 constexpr int kAttn128Bufs = 3;          // K and V tiles are triple buffered
 constexpr int kAttn128Smem = 2 * kAttn128Bufs * kTileBytes;
+constexpr int kSweepBufs = 6;            // importance sweep: K tiles rotate through six buffers,
+constexpr int kSweepAhead = 5;           //   tile t+5 is requested while tile t is summed
+constexpr int kAttn128SweepSmem = (kSweepBufs + 1) * kTileBytes;   // + exchange area
 constexpr float kLazyLog2 = 8.0f;        // a row's softmax reference may lag its running max by a factor 2^8
 
 __device__ __forceinline__ int swz16(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
@@ -75,7 +78,7 @@ __device__ __forceinline__ bf16x8 lds_read_tr8(uint32_t lo, uint32_t hi)
     return __builtin_bit_cast(bf16x8, c);
 }
 
-template <int NWAVES>
+template <int NWAVES, bool IMP = false>
 __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_fwd_d128_kernel(const AttnParams p)
 {
@@ -100,10 +103,17 @@ void attn_fwd_d128_kernel(const AttnParams p)
     const int ks = min(p.cu_k[b], p.total_k), ke = min(p.cu_k[b + 1], p.total_k);
     const int nq = qe - qs, nk = ke - ks;
     const int m0 = t * BM;
-    if (m0 >= nq || nq <= 0) return;
+    const int tid = threadIdx.x;
+    // importance sweep: this workgroup's slice of the partial column sums, at its sequence
+    float *const part_row = IMP
+        ? p.imp_part + ((int64_t)(hg * p.n_qtiles + t) * p.Hkv + g) * p.total_k + ks : nullptr;
+    if (m0 >= nq || nq <= 0) {
+        if constexpr (IMP)   // no query rows here: the slice still has to read as zero
+            for (int j = tid; j < nk; j += NWAVES * 64) part_row[j] = 0.f;
+        return;
+    }
     const int delta = nk - nq;
 
-    const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hh = lane >> 5;
@@ -454,6 +464,164 @@ void attn_fwd_d128_kernel(const AttnParams p)
                 : -INFINITY;
             p.lse[(int64_t)h * p.total_q + qs + qrow] = lse;
         }
+    }
+
+    // ---- importance sweep (paper Section 3.2, token importance of an observation window that
+    // covers every query of the call): with the final log-sum-exp of its 32 rows in hand, each
+    // wave walks the same K tiles again, recomputes S = Q K^T with the operands exchanged (lane =
+    // key, registers = the wave's 32 query rows), turns it into the normalised probabilities and
+    // adds them up along the query dimension.  The eight waves' column sums of a 64-key tile meet
+    // in LDS; one wave adds them in the fixed order wave 0, 1, ... and writes the tile's 64 sums.
+    // No atomics: the result does not depend on timing.
+    if constexpr (IMP) {
+        // LDS: K tiles now rotate through kSweepBufs buffers (the K and V buffers of the first
+        // sweep, contiguous); the log-sum-exp exchange and the column sums lie behind them.  A step
+        // is short (16 MFMAs per wave), so a tile is requested five steps before its first use and
+        // the wait at the end of a step leaves the two youngest requests in flight.
+        float *lse_sh = (float *)(smem128 + kSweepBufs * kTileBytes);          // [NWAVES][32]
+        float *red = (float *)(smem128 + kSweepBufs * kTileBytes + 1024);      // [2][NWAVES][64]
+        // a row's probabilities are 2^(s * c2 - lse2); rows past the end or without a visible key give 0
+        const float lse2 = (qrow < nq && l_tot > 0.f) ? __builtin_amdgcn_logf(l_tot) - ref : INFINITY;
+        if (hh == 0) lse_sh[wave * 32 + n] = lse2;
+        for (int tl = 0; tl < kSweepAhead; ++tl) issue_k(tl, tl);   // tiles past the end read as zero
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        float nl[16];                              // minus lse2 of the rows this lane's registers hold
+#pragma unroll
+        for (int bq = 0; bq < 4; ++bq) {
+            const f32x4 x = *(const f32x4 *)(lse_sh + wave * 32 + 8 * bq + 4 * hh);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) nl[4 * bq + r] = -x[r];
+        }
+        // S of the 32-key block at byte offset `koff`: rows 8 (e / 4) + 4 hh + e % 4 of the wave, key n
+        auto qk_rows = [&](uint32_t koff, f32x16 &s) {
+            const uint8_t *kb = Ks + koff;
+#pragma unroll
+            for (int kk = 0; kk < NKK; ++kk) {
+                const bf16x8 kfrag = *(const bf16x8 *)(kb + kaddr[kk]);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], kfrag, kk == 0 ? zero16 : s, 0, 0, 0);
+            }
+        };
+        // this lane's share (16 of the wave's 32 rows) of the probabilities of key j0 + n
+        auto half_sum = [&](const float (&c)[4]) { return (c[0] + c[1]) + (c[2] + c[3]); };
+        auto col_sum = [&](const f32x16 &s, const int j0) {
+            float c[4] = {0.f, 0.f, 0.f, 0.f};
+            if (j0 + 31 > wave_lim_min) {          // the block touches the diagonal (or the end of K)
+                const int jj = j0 + n - delta - wave_q0 - 4 * hh;   // visible to row r iff jj <= r - 4 hh
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float pe = fast_exp2(fmaf(s[e], c2, nl[e]));
+                    c[e & 3] += (jj <= 8 * (e >> 2) + (e & 3)) ? pe : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) c[e & 3] += fast_exp2(fmaf(s[e], c2, nl[e]));
+            }
+            return half_sum(c);
+        };
+        // x0 / x1: the lane's shares for the tile's first / second 32-key block.  One half-wave swap
+        // completes both sums at once: afterwards lane l holds the wave's column sum of key l of
+        // the tile.  The waves' sums meet in LDS as red[tile parity][key][wave]; after the barrier
+        // (which also publishes a K tile) wave it2 % NWAVES adds the NWAVES values of each key in
+        // the fixed order wave 0, 1, ... and stores the tile's 64 sums.
+        auto tile_done = [&](const int it2, const float x0, const float x1) {
+            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x0), __float_as_uint(x1), false, false);
+            red[(((it2 & 1) * 64 + lane) * NWAVES) + wave] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+            // every step requests one tile (NLD loads per wave): all but the two youngest requests
+            // have landed, i.e. the tiles up to it2 + 3; a store of the summing wave in between
+            // only makes the wait stricter
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(2 * NLD) : "memory");
+            __syncthreads();
+            if (wave == it2 % NWAVES) {
+                f32x4 v[NWAVES / 4];
+#pragma unroll
+                for (int q = 0; q < NWAVES / 4; ++q)
+                    v[q] = *(const f32x4 *)(red + (((it2 & 1) * 64 + lane) * NWAVES) + 4 * q);
+                float acc = v[0][0];
+#pragma unroll
+                for (int w = 1; w < NWAVES; ++w) acc += v[w / 4][w % 4];
+                const int j = 64 * it2 + lane;
+                if (j < nk) part_row[j] = acc;
+            }
+        };
+        // At the top of step it2 the scores of tile it2 are in registers, tiles it2+1 and it2+2 are
+        // in LDS (tile t in buffer t % kSweepBufs) and tiles it2+3, it2+4 are requested.
+        f32x16 sa[2] = {zero16, zero16}, sb[2] = {zero16, zero16};
+        if (n_tiles > 0) {
+            qk_rows(0, sa[0]);
+            qk_rows(32 * 256, sa[1]);
+        }
+        int it2 = 0;
+        // Tiles every row of the workgroup sees in full and that have a successor (the same ones as
+        // in the first sweep): no masks.  While the probabilities of tile it2 are summed, the 16
+        // MFMAs of tile it2+1 are issued, alternating between its two 32-key blocks so that
+        // consecutive MFMAs are independent; each K fragment is read four MFMAs before its use.
+        bf16x8 fr[4];
+        auto frag_at = [&](uint32_t tile_off, int i) {
+            return *(const bf16x8 *)(Ks + tile_off + (i & 1) * 32 * 256 + kaddr[i >> 1]);
+        };
+        auto sweep_step = [&](auto par_c, const f32x16 (&sc)[2], f32x16 (&sn)[2]) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(par_c)::value;      // it2 % kSweepBufs
+            constexpr uint32_t T1 = (uint32_t)((PAR + 1) % kSweepBufs) * kTileBytes;
+            constexpr uint32_t T2 = (uint32_t)((PAR + 2) % kSweepBufs) * kTileBytes;
+            issue_k(it2 + kSweepAhead, (PAR + kSweepAhead) % kSweepBufs);
+            float c[2][4];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int blk = i & 1, kk = i >> 1;
+                sn[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], fr[i & 3], kk == 0 ? zero16 : sn[blk], 0, 0, 0);
+                fr[i & 3] = i + 4 < 16 ? frag_at(T1, i + 4) : frag_at(T2, i + 4 - 16);
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    const int cb = i >> 3, e = 2 * (i & 7) + x;
+                    const float pe = fast_exp2(fmaf(sc[cb][e], c2, nl[e]));
+                    c[cb][e & 3] = e < 4 ? pe : c[cb][e & 3] + pe;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // 2 multiply-adds
+                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // 2 transcendental
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // 2 additions
+            }
+            tile_done(it2, half_sum(c[0]), half_sum(c[1]));
+            ++it2;
+        };
+        if (n_hot > 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fr[i] = frag_at(kTileBytes, i);
+            while (it2 + 6 <= n_hot) {
+                sweep_step(std::integral_constant<int, 0>{}, sa, sb);
+                sweep_step(std::integral_constant<int, 1>{}, sb, sa);
+                sweep_step(std::integral_constant<int, 2>{}, sa, sb);
+                sweep_step(std::integral_constant<int, 3>{}, sb, sa);
+                sweep_step(std::integral_constant<int, 4>{}, sa, sb);
+                sweep_step(std::integral_constant<int, 5>{}, sb, sa);
+            }
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 0>{}, sa, sb);
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 1>{}, sb, sa);
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 2>{}, sa, sb);
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 3>{}, sb, sa);
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 4>{}, sa, sb);
+            if (n_hot & 1) { sa[0] = sb[0]; sa[1] = sb[1]; }
+        }
+        // the diagonal region; sa holds the scores of its first tile
+        for (; it2 < n_tiles; ++it2) {
+            issue_k(it2 + kSweepAhead, (it2 + kSweepAhead) % kSweepBufs);
+            const float c0 = col_sum(sa[0], 64 * it2);
+            const float c1 = col_sum(sa[1], 64 * it2 + 32);
+            tile_done(it2, c0, c1);
+            if (it2 + 1 < n_tiles) {
+                const uint32_t b1 = (uint32_t)((it2 + 1) % kSweepBufs) * kTileBytes;
+                qk_rows(b1, sa[0]);
+                qk_rows(b1 + 32 * 256, sa[1]);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);   // requests past the last tile are still in flight
+        // keys that no query of this tile can see
+        for (int j = 64 * n_tiles + tid; j < nk; j += NWAVES * 64) part_row[j] = 0.f;
     }
 #else
     (void)p;

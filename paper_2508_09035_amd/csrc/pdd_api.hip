@@ -22,7 +22,7 @@
 // Scratch of the allocation-free entry point: one copy per GPU the library runs on, held until
 // the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the address
 // that kernels and memory calls use is the one that call returns for the current device.
-#define PDD_STATIC_SCRATCH_BYTES (4u << 20)
+#define PDD_STATIC_SCRATCH_BYTES (16u << 20)
 static __device__ __align__(256) unsigned char scratch[PDD_STATIC_SCRATCH_BYTES];
 
 namespace {
@@ -140,17 +140,52 @@ pdd_status launch_attn_kernel(Kern kern, int smem, int threads, const pdd::AttnP
 template <int D, int NW>
 pdd_status launch_attn_t(const pdd::AttnParams &p, int64_t blocks, hipStream_t st)
 {
-    if constexpr (D == 128)
+    if constexpr (D == 128) {
+        if (p.imp_part)
+            return launch_attn_kernel(pdd::attn_fwd_d128_kernel<NW, true>, pdd::kAttn128SweepSmem, NW * 64, p, blocks, st);
         return launch_attn_kernel(pdd::attn_fwd_d128_kernel<NW>, pdd::kAttn128Smem, NW * 64, p, blocks, st);
-    else
+    } else
         return launch_attn_kernel(pdd::attn_fwd_kernel<D, NW>, pdd::AttnSmem<D>::BYTES, NW * 64, p, blocks, st);
 }
 
+// Queries per attention workgroup: 8 waves (256 queries) halve the K/V traffic per flop; they
+// are used when there are enough such workgroups for half of the 256 CUs (measured break-even),
+// else 4 waves.
+int attn_rows_per_workgroup(const pdd_attn_desc *d)
+{
+    int nw = g_attn_waves;
+    const int64_t tiles256 = (int64_t)((d->max_seqlen_q + 255) / 256) * d->batch * d->n_q_heads;
+    if (nw == 0) nw = tiles256 >= 128 ? 8 : 4;
+    return nw * 32;
+}
+
+// Chunked mode with head_dim 128 can take the token importance from a second sweep inside the
+// attention kernel (every query of the call is a window query there).  Its partial sums need one
+// float per (query head, query tile, key); 0 = this shape does not use the sweep.
+constexpr size_t kSweepWorkspaceMax = (size_t)256 << 20;
+size_t sweep_workspace(const pdd_attn_desc *d)
+{
+    if (d->head_dim != 128 || d->total_q == 0 || d->total_k == 0) return 0;
+    const int bm = attn_rows_per_workgroup(d);
+    const size_t n_qtiles = (size_t)((d->max_seqlen_q + bm - 1) / bm);
+    const size_t need = n_qtiles * d->n_q_heads * (size_t)d->total_k * sizeof(float);
+    return need <= kSweepWorkspaceMax ? need : 0;
+}
+
+void launch_importance_reduce(const float *part, float *imp, int64_t n, int n_split, hipStream_t st)
+{
+    hipLaunchKernelGGL(pdd::importance_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       part, imp, n, n_split);
+}
+
+// imp_part != NULL: head_dim 128 only, sweep_workspace(d) bytes; the importance sweep runs inside
+// the attention kernel and leaves its partial sums there.
 pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, const void *v, void *o, float *lse,
-                       hipStream_t st)
+                       hipStream_t st, float *imp_part = nullptr)
 {
     if (d->total_q == 0) return PDD_OK;
     pdd::AttnParams p;
+    p.imp_part = imp_part;
     p.q = (const uint16_t *)q;  p.k = (const uint16_t *)k;  p.v = (const uint16_t *)v;
     p.o = (uint16_t *)o;  p.lse = lse;
     p.cu_q = d->cu_seqlens_q;  p.cu_k = d->cu_seqlens_k;
@@ -162,18 +197,15 @@ pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, con
     p.total_q = d->total_q;  p.total_k = d->total_k;
     p.scale_log2 = scale_log2(d);
 
-    // 8 waves (256 queries per workgroup) halve the K/V traffic per flop; use them when there
-    // are enough such workgroups for half of the 256 CUs (measured break-even), else 4 waves.
-    int nw = g_attn_waves;
-    const int64_t tiles256 = (int64_t)((d->max_seqlen_q + 255) / 256) * d->batch * d->n_q_heads;
-    if (nw == 0) nw = tiles256 >= 128 ? 8 : 4;
-    const int bm = nw * 32;
+    const int bm = attn_rows_per_workgroup(d);
+    const int nw = bm / 32;
     p.n_qtiles = (d->max_seqlen_q + bm - 1) / bm;
     const int64_t blocks = (int64_t)p.n_qtiles * d->batch * d->n_q_heads;
     if (blocks > 0x7fffffffLL) return fail(PDD_ERR_INVALID_ARG, "launch grid too large");
     if (d->head_dim == 128) {
         // 32-bit byte offsets inside one sequence's K / V span (buffer addressing)
-        const int64_t span = ((int64_t)d->max_seqlen_k + 64) * 2 *
+        // (the kernels request up to six tiles of 64 rows past a sequence's end, which read as zero)
+        const int64_t span = ((int64_t)d->max_seqlen_k + 512) * 2 *
                              (d->k_stride_tok > d->v_stride_tok ? d->k_stride_tok : d->v_stride_tok);
         if (span >= (1LL << 32)) return fail(PDD_ERR_UNSUPPORTED, "a sequence's K/V span must stay below 4 GiB");
         return nw == 8 ? launch_attn_t<128, 8>(p, blocks, st) : launch_attn_t<128, 4>(p, blocks, st);
@@ -267,14 +299,18 @@ pdd_status launch_importance(const pdd_attn_desc *d, const void *q, const void *
         hipLaunchKernelGGL(pdd::importance_kernel<128>, dim3((unsigned)blocks), dim3(pdd::kImpWaves * 64), 0, st, p);
     else
         hipLaunchKernelGGL(pdd::importance_kernel<64>, dim3((unsigned)blocks), dim3(pdd::kImpWaves * 64), 0, st, p);
-    if (split) {
-        const int64_t n = (int64_t)d->n_kv_heads * d->total_k;
-        hipLaunchKernelGGL(pdd::importance_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                           p.part, imp, n, p.n_split);
-    }
+    if (split) launch_importance_reduce(p.part, imp, (int64_t)d->n_kv_heads * d->total_k, p.n_split, st);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(PDD_ERR_HIP, "importance launch: %s", hipGetErrorString(e));
     return PDD_OK;
+}
+
+// What the chunked call can use: room for the in-kernel sweep where that applies, else for the
+// row split of the separate importance kernel.
+size_t chunked_workspace(const pdd_attn_desc *d)
+{
+    const size_t sweep = sweep_workspace(d);
+    return sweep ? sweep : importance_workspace(d, -1);
 }
 
 // Device address of this GPU's copy of `scratch`, looked up once per device.
@@ -333,7 +369,7 @@ size_t pdd_workspace_bytes(const pdd_attn_desc *desc, int which_call)
     case PDD_CALL_PREFILL_ATTN:
         return desc->window > 0 ? importance_workspace(desc, desc->window) : 0;
     case PDD_CALL_PREFILL_ATTN_CHUNKED:
-        return importance_workspace(desc, -1);
+        return chunked_workspace(desc);
     case PDD_CALL_TOKEN_IMPORTANCE:
         return desc->window != 0 ? importance_workspace(desc, desc->window) : 0;
     default:
@@ -367,6 +403,20 @@ pdd_status pdd_prefill_attn_chunked(const pdd_attn_desc *desc, const void *q_chu
     if (s) return s;
     s = check_ptrs(q_chunk, k_all, v_all, o, lse);
     if (s) return s;
+    const size_t sweep = importance ? sweep_workspace(desc) : 0;
+    if (sweep && workspace && workspace_bytes >= sweep) {
+        if (reinterpret_cast<uintptr_t>(workspace) & 15u)
+            return fail(PDD_ERR_WORKSPACE, "workspace must be 16-byte aligned");
+        s = launch_attn(desc, q_chunk, k_all, v_all, o, lse, (hipStream_t)stream, (float *)workspace);
+        if (s) return s;
+        const int bm = attn_rows_per_workgroup(desc);
+        const int n_slices = (desc->n_q_heads / desc->n_kv_heads) * ((desc->max_seqlen_q + bm - 1) / bm);
+        launch_importance_reduce((const float *)workspace, importance, (int64_t)desc->n_kv_heads * desc->total_k,
+                                 n_slices, (hipStream_t)stream);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(PDD_ERR_HIP, "importance reduction launch: %s", hipGetErrorString(e));
+        return PDD_OK;
+    }
     s = launch_attn(desc, q_chunk, k_all, v_all, o, lse, (hipStream_t)stream);
     if (s) return s;
     if (importance)
@@ -381,7 +431,7 @@ pdd_status pdd_prefill_attn_chunked_noalloc(const pdd_attn_desc *desc, const voi
 {
     pdd_status s = check_desc(desc, MODE_CHUNKED);
     if (s) return s;
-    const size_t need = importance ? importance_workspace(desc, -1) : 0;
+    const size_t need = importance ? chunked_workspace(desc) : 0;
     if (need > PDD_STATIC_SCRATCH_BYTES)
         return fail(PDD_ERR_WORKSPACE, "this shape wants %zu bytes of scratch, the built-in scratch holds %u "
                     "(use pdd_prefill_attn_chunked with a workspace)", need, (unsigned)PDD_STATIC_SCRATCH_BYTES);

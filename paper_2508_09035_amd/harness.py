@@ -34,8 +34,8 @@ class DeviceWorkload:
         self.total_keep = int(wl.cu_keep[-1])
         self.idx = torch.empty((wl.n_kv_heads, self.total_keep), dtype=torch.int32, device="cuda")
         self.mask = torch.empty((wl.n_kv_heads, wl.total_k), dtype=torch.uint8, device="cuda")
-        # scratch for the calls that can use one (the importance step divides its window rows over
-        # several workgroups when it gets room for their partial sums)
+        # scratch for the calls that can use one (partial importance sums: of the sweep inside the
+        # attention kernel in chunked mode, else of the importance kernel's row split)
         desc, keep = pdd.make_desc(self.q, self.k, self.v, self.o, self.cu_q, self.cu_k, self.max_q, self.max_k,
                                    wl.scale, wl.window)
         call = pdd.CALL_PREFILL_ATTN_CHUNKED if wl.chunked else pdd.CALL_PREFILL_ATTN
@@ -56,7 +56,10 @@ class DeviceWorkload:
         wl = self.wl
         hq = wl.cu_seqlens_q if host_cu else None
         hk = wl.cu_seqlens_k if host_cu else None
+        # use_workspace: True = all of it, False = none, an int = only that many bytes of it
         ws = self.workspace if use_workspace else None
+        if ws is not None and use_workspace is not True:
+            ws = ws[:int(use_workspace)]
         if wl.chunked:
             pdd.prefill_attn_chunked(self.q, self.k, self.v, self.o, self.lse,
                                      self.imp if with_importance else None, self.cu_q, self.cu_k,

@@ -242,7 +242,7 @@ def test_workspace_bytes_host_only():
 
 def test_noalloc_rejects_shapes_beyond_its_scratch():
     """The allocation-free chunked entry point refuses, on the host, a shape whose scratch
-    would not fit its built-in 4 MiB array: nothing is launched."""
+    would not fit its built-in 16 MiB array: nothing is launched."""
     d = AttnDesc()
     d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = 4, 128, 8, 128     # 16 query heads per KV head, chunks of 1024
     d.total_q, d.max_seqlen_q, d.total_k, d.max_seqlen_k = 4 * 1024, 1024, 4 * 8448, 8448

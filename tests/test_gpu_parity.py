@@ -165,26 +165,44 @@ def test_standalone_importance_equals_fused_and_is_deterministic():
     assert (dev.imp == -5.0).all()
 
 
-@pytest.mark.parametrize("name", ["c5", "chunk-ragged"])
+@pytest.mark.parametrize("name", ["c5", "chunk-ragged", "chunk-tiles", "chunk-d64"])
 def test_importance_with_and_without_scratch(name):
-    """The importance step with its window rows divided over several workgroups (partial sums in
-    the caller's scratch, added in a fixed order) and as a single pass without scratch: both
-    against the oracle."""
+    """The three forms of the importance step in chunked mode, each against the oracle: as a
+    second sweep inside the attention kernel (head_dim 128, all of the scratch the library asks
+    for), as the separate kernel with its window rows divided over several workgroups (one byte
+    less than that, or head_dim 64), and as the separate kernel in a single pass (no scratch).
+    Partial sums live in the caller's scratch and are added in a fixed order."""
     if name == "c5":
         wl = W.make_workload(name)
-    else:       # ragged chunks with 16 query heads per KV head, long enough for the split to pay
+    elif name == "chunk-ragged":   # ragged chunks with 16 query heads per KV head
         wl = W.make_custom("t", [200, 256, 77, 256], [200 + 9000, 256 + 7000, 77 + 8000, 256 + 8100], 32, 2, 128, 0,
                            "1/4", seed=41, chunked=True)
-    dev = DeviceWorkload(wl)
-    assert dev.workspace_bytes > 0          # these shapes are split
+    elif name == "chunk-tiles":    # chunks of several 256-row query tiles, one of them a single row,
+        wl = W.make_custom("t", [700, 1, 513, 256], [700 + 1500, 1 + 900, 513, 256 + 64], 8, 2, 128, 0,   # one without a prefix
+                           "1/4", seed=43, chunked=True)
+    else:                          # head_dim 64 has no sweep: the row split takes all of the scratch
+        wl = W.make_custom("t", [256, 200, 256, 256], [256 + 8000, 200 + 9000, 256 + 8100, 256 + 7000], 32, 2, 64, 0,
+                           "1/4", seed=47, chunked=True)
     oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, -1 if wl.chunked else wl.window)
-    for use_ws in (True, False):
-        dev.poison()
-        if dev.workspace is not None:
-            dev.workspace.fill_(0xFF)       # NaN patterns: a partial sum that is not overwritten shows
-        dev.attn(True, use_workspace=use_ws)
-        torch.cuda.synchronize()
-        rel_close(dev.imp.cpu().numpy().astype(np.float64), oI, f"{name} importance, scratch={use_ws}")
+    oO, oL = oracle.attention(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale) if name == "chunk-tiles" else (None, None)
+    try:
+        for waves in ((4, 8) if name == "chunk-tiles" else (0,)):      # 128 and 256 query rows per workgroup
+            pdd.set_option(pdd.OPT_ATTN_WAVES, waves)
+            dev = DeviceWorkload(wl)                                     # sizes its scratch for this option
+            assert dev.workspace_bytes > 0
+            for use_ws in (True, dev.workspace_bytes - 1, False):
+                what = f"{name} waves={waves} scratch={use_ws}"
+                dev.poison()
+                dev.workspace.fill_(0xFF)   # NaN patterns: a partial sum that is not overwritten shows
+                dev.attn(True, use_workspace=use_ws)
+                torch.cuda.synchronize()
+                rel_close(dev.imp.cpu().numpy().astype(np.float64), oI, what + " importance")
+                if oO is not None:          # the sweep must leave the attention output alone
+                    O, lse = dev.results()[:2]
+                    assert np.abs(O - oO).max() <= O_ATOL, what + " O"
+                    rel_close(lse, oL, what + " lse")
+    finally:
+        pdd.set_option(pdd.OPT_ATTN_WAVES, 0)
 
 
 @pytest.mark.parametrize("name", ["c5", "c3", "c4"])
