@@ -279,6 +279,23 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
     return x;
 }
 
+// Next value to probe in the threshold search over the bracket [lo, hi] (lo < hi) that holds
+// `inside` keys, of which the `need` largest (1 <= need <= inside) lie at or above the threshold.
+// With interpolate set, the keys are taken as evenly spread over the bracket, which is nearly true
+// once the bracket is a narrow slice of the score distribution, and the probe lands a few keys
+// away from the threshold instead of halving the bracket; otherwise the bracket is bisected.  The
+// callers interpolate as long as the previous probe cut the number of keys in the bracket to a
+// quarter or less and bisect after one that did not, which bounds the worst case at twice the
+// probes of plain bisection.  The result is in [lo + 1, hi]: either outcome shrinks the bracket.
+__device__ __forceinline__ uint32_t next_probe(uint32_t lo, uint32_t hi, uint32_t inside, uint32_t need, bool interpolate)
+{
+    const uint32_t span = hi - lo;
+    if (!interpolate) return lo + ((span + 1u) >> 1);
+    const float f = ((float)need - 0.5f) / (float)inside;          // share of the bracket above the threshold
+    const uint32_t down = (uint32_t)min(f * (float)span, 4294967040.f);
+    return hi - min(down, span - 1u);
+}
+
 template <int QPT>
 __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const SelParams p)
 {
@@ -374,8 +391,10 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
     uint32_t lo = kmin, hi = kmax;
     uint32_t c_lo = (uint32_t)n, c_above = 0;
     int par = 0;
+    bool interp = true;
     while (lo < hi && c_lo - c_above > (uint32_t)kSelWaveKeys) {
-        const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+        const uint32_t inside = c_lo - c_above;
+        const uint32_t mid = next_probe(lo, hi, inside, (uint32_t)kk - c_above, interp);
         uint32_t c = (uint32_t)__popcll(__ballot(khead >= mid));
 #pragma unroll
         for (int i = 0; i < QPT; ++i)
@@ -389,6 +408,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
         par ^= 1;
         if (tot >= (uint32_t)kk) { lo = mid; c_lo = tot; }
         else { hi = mid - 1u; c_above = tot; }
+        interp = !interp || 4u * (c_lo - c_above) <= inside;
     }
     if (lo < hi) {
         // ---- the keys still inside [lo, hi] (at most kSelWaveKeys) go to LDS, in any order ...
@@ -401,11 +421,13 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
         const uint32_t incl = wave_incl_scan(mine);
         if (lane == 63) cnt_wave_tot[wave] = incl;
         __syncthreads();
-        uint32_t pos = incl - mine;
-        for (int w = 0; w < wave; ++w) pos += cnt_wave_tot[w];
-        uint32_t m_tot = 0;
+        uint32_t pos = incl - mine, m_tot = 0;
 #pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) m_tot += cnt_wave_tot[w];
+        for (int w = 0; w < kSelWaves; ++w) {               // independent reads, no trip count to wait for
+            const uint32_t t = cnt_wave_tot[w];
+            pos += w < wave ? t : 0u;
+            m_tot += t;
+        }
         if (khead >= lo && khead <= hi) fin_keys[pos++] = khead;
 #pragma unroll
         for (int i = 0; i < QPT; ++i)
@@ -424,13 +446,20 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
             const uint32_t r = (uint32_t)kk - c_above;              // 1 <= r <= m_tot
             uint32_t wlo = lo, whi = hi;
             uint32_t w_ge = m_tot, above = 0;                       // count(key >= wlo), count(key > whi)
+            bool winterp = true;
             while (wlo < whi && w_ge - above > (uint32_t)kSelFinish) {
-                const uint32_t mid = wlo + ((whi - wlo + 1u) >> 1);
-                uint32_t c = 0;
+                const uint32_t inside = w_ge - above;
+                const uint32_t mid = next_probe(wlo, whi, inside, r - above, winterp);
+                // per-lane counts on four independent chains, one wave sum at the end (a ballot and
+                // a scalar population count per key would wait for each other with one wave running)
+                uint32_t cl[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-                for (int t = 0; t < KPL; ++t) c += (uint32_t)__popcll(__ballot(fk[t] >= mid));
+                for (int t = 0; t < KPL; ++t) cl[t & 3] += fk[t] >= mid ? 1u : 0u;
+                const uint32_t c = (uint32_t)__builtin_amdgcn_readlane(
+                    (int)wave_incl_scan((cl[0] + cl[1]) + (cl[2] + cl[3])), 63);
                 if (c >= r) { wlo = mid; w_ge = c; }
                 else { whi = mid - 1u; above = c; }
+                winterp = !winterp || 4u * (w_ge - above) <= inside;
             }
             uint32_t T_w = wlo;
             if (wlo < whi) {
@@ -481,10 +510,9 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
     for (int i = 0; i < QPT; ++i) {
         uint32_t c = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool in = 4 * (i * kSelThreads + tid) + j < nq_el;
-            c += (in && key[i][j] > T) ? 1u : 0u;
-            c += (in && key[i][j] == T) ? 0x10000u : 0u;
+        for (int j = 0; j < 4; ++j) {                  // empty slots hold key 0 < kmin <= T
+            c += key[i][j] > T ? 1u : 0u;
+            c += key[i][j] == T ? 0x10000u : 0u;
         }
         const uint32_t incl = wave_incl_scan(c);
         pre[i] = incl - c;
@@ -518,8 +546,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
         uint32_t mbytes = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const bool in = x0 + j < nq_el;
-            const bool is_gt = in && key[i][j] > T, is_eq = in && key[i][j] == T;
+            const bool is_gt = key[i][j] > T, is_eq = key[i][j] == T;    // never true for an empty slot
             const bool sel = is_gt || (is_eq && eq_before < krem);
             if (sel) out[gt_before + min(eq_before, krem)] = c0 + nhead + x0 + j;
             gt_before += is_gt ? 1 : 0;
