@@ -29,7 +29,7 @@ OTHERS = ("c1", "c2", "c3", "c5")
 # HBM bytes per launch of the attention kernel (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc runs, each
 # scaled by the same counter's reading for a 1 GiB device copy; see profiles/).  Valid only for the
 # kernel sources with this digest: once they change the figure is reported as null.
-KERNEL_SOURCES = ("attn_fwd_d128.hpp", "attn_fwd.hpp")
+KERNEL_SOURCES = ("attn_fwd.hpp",)
 TRAFFIC = {"c4": {"bytes": 1.679e9, "sources_sha256": "f4ab1cf7bfb6ee6e96fc40885120b3e164725c097907385877747afe774eb766"}}
 
 O_ATOL, REL = 2e-2, 1e-3       # the parity bar: O max-abs, log-sum-exp / importance relative
@@ -228,7 +228,7 @@ def run_config(name, args, budget_gflop, with_cpu_baseline):
                     "select+compaction": round(ms_select, 4)},
         "select_GBps": round(sel_bytes / (ms_select * 1e-3) / 1e9, 2),
         "roofline": {"bound": "mfma",
-                     "kernel": "attn_fwd_d128_kernel" if wl.head_dim == 128 else "attn_fwd_kernel",
+                     "kernel": "attn_fwd_kernel",
                      "achieved": round(tflops_attn, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 4),
                      "traffic": traffic},

@@ -1,4 +1,4 @@
-// Causal / GQA / ragged prefill attention for gfx950 (flash-style forward).
+// Causal / GQA / ragged prefill attention for gfx950 (flash-style forward), head_dim 64 or 128.
 //
 // Computes, per sequence b, query head h (KV head g = h / G) and query i,
 //   S[i,j] = s <q_i, k_j>  for j <= i + delta_b,   lse = ln sum_j exp S[i,j],
@@ -9,18 +9,34 @@
 //
 // Work decomposition
 //   workgroup = NWAVES wavefronts, each owning 32 consecutive queries of one
-//   (sequence, query head); key/value tiles of 64 keys stream through LDS
-//   (double buffered, register-staged prefetch of the next tile).
+//   (sequence, query head); key/value tiles of 64 keys stream through LDS.
 //   Per 32-key block a wave computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16
 //   (A = K rows from LDS, B = Q fragments held in registers), so lane l owns
 //   query (l % 32) and the 16 accumulator registers hold 16 different keys:
 //   row max / row sum are in-lane reductions plus one exchange between lanes
 //   l and l+32.  O^T = V^T P^T reuses those registers directly as the B
-//   operand (the contraction index "key" may be permuted freely as long as V^T
-//   is stored with the same permutation in LDS).
+//   operand (the contraction index "key" may be permuted freely as long as the
+//   V^T fragments are read with the same permutation).
+//
+// Data movement and instruction schedule
+//   * K and V tiles (64 keys x 2 D bytes) go from HBM/L2 straight into LDS with
+//     buffer_load ... lds (no staging registers, no ds_write); rows past the
+//     end of the sequence read as zero through the buffer bounds check.
+//   * Both tiles are row-major in LDS with a 16-byte-chunk XOR swizzle,
+//       D = 128 (16 chunks per row):  chunk' = chunk ^ (((row & 3) << 2) | ((row >> 2) & 3))
+//       D = 64  (8 chunks per row):   chunk' = chunk ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3))
+//     which makes the K fragment reads (ds_read_b128, 16 rows per quarter
+//     wave) and the V^T fragment reads (ds_read_b64_tr_b16, 4 rows x 64 B per
+//     32 lanes) bank-conflict free without padding.
+//   * V is transposed on the fly by the LDS transpose read, so V needs no
+//     register shuffle.
+//   * The loop is software pipelined: the QK^T MFMAs of block j+1 are issued
+//     together with the softmax VALU work of block j, then the PV MFMAs of
+//     block j follow.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace pdd {
 
@@ -48,15 +64,6 @@ struct AttnParams {
 
 constexpr int kBN = 64;  // keys per LDS tile
 
-template <int D>
-struct AttnSmem {
-    static constexpr int KSTR = D + 8;    // bf16 elements per K row (16 B pad)
-    static constexpr int VSTR = kBN + 8;  // bf16 elements per V^T row
-    static constexpr int K_ELEMS = kBN * KSTR;
-    static constexpr int V_ELEMS = D * VSTR;
-    static constexpr int BYTES = 2 * (K_ELEMS + V_ELEMS) * 2;
-};
-
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float max3(float a, float b, float c)
@@ -77,24 +84,88 @@ __device__ __forceinline__ float xchg_half(float x)
     return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
-template <int D, int NWAVES>
-__global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(const AttnParams p)
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+constexpr int kAttnBufs = 3;             // K and V tiles are triple buffered
+constexpr int kSweepBufs = 6;            // importance sweep: K tiles rotate through six buffers,
+constexpr int kSweepAhead = 5;           //   tile t+5 is requested while tile t is summed
+template <int D>
+struct AttnSmem {
+    static constexpr int TILE = kBN * D * 2;                       // one K or V tile in LDS, bytes
+    static constexpr int BYTES = 2 * kAttnBufs * TILE;
+    static constexpr int SWEEP_BYTES = (kSweepBufs + 1) * TILE;    // + exchange area
+};
+constexpr float kLazyLog2 = 8.0f;        // a row's softmax reference may lag its running max by a factor 2^8
+
+// chunk swizzle of LDS row `row` (see the head of this file)
+template <int D>
+__device__ __forceinline__ int swz_row(int row)
 {
-    using SM = AttnSmem<D>;
-    constexpr int NT = NWAVES * 64;
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+
+typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
+
+// Raw buffer descriptor (base, num_records in bytes, untyped dword access) held in SGPRs.
+__device__ __forceinline__ i32x4 make_rsrc(const void *base, uint32_t bytes)
+{
+    const uint64_t a = (uint64_t)base;
+    i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int32_t)(uint32_t)a);
+    r.y = __builtin_amdgcn_readfirstlane((int32_t)((uint32_t)(a >> 32) & 0xffffu));
+    r.z = __builtin_amdgcn_readfirstlane((int32_t)bytes);
+    r.w = 0x00020000;
+    return r;
+}
+
+// 16 bytes per lane from the buffer straight into LDS at lds_addr + 16 * lane
+// (lds_addr wave-uniform).  Out-of-range lanes write zeros.  Written as inline
+// assembly so that the transfer stays asynchronous: completion is awaited with
+// an explicit s_waitcnt vmcnt(0) before the workgroup barrier that publishes
+// the tile.  M0 is declared clobbered, so the compiler neither keeps a value in it across
+// the transfer nor misses the wait state after the write.
+__device__ __forceinline__ void dma16_to_lds(i32x4 rsrc, uint32_t lds_addr, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t *)p;
+}
+
+__device__ __forceinline__ bf16x8 lds_read_tr8(uint32_t lo, uint32_t hi)
+{
+    // two transposing 64-bit reads -> 8 bf16 (k-slots 0..3 from lo, 4..7 from hi); lo / hi are
+    // LDS byte addresses, so that constant parts fold into the instruction's offset field
+    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(uintptr_t)lo);
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(uintptr_t)hi);
+    const s16x8 c = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, c);
+}
+
+template <int D, int NWAVES, bool IMP = false>
+__global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_fwd_kernel(const AttnParams p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)   // the body uses gfx950-only types; the host pass needs the stub only
+    static_assert(D == 64 || D == 128, "head_dim 64 or 128");
+    constexpr int ROWB = 2 * D;                 // bytes of one K or V row
+    constexpr int CH = D / 8;                   // 16-byte chunks per row
+    constexpr int RPI = 1024 / ROWB;            // rows one buffer_load ... lds instruction fills
+    constexpr int kTileBytes = AttnSmem<D>::TILE;
     constexpr int BM = NWAVES * 32;
-    constexpr int KCH = D / 8;                       // 16-byte chunks per K row
-    constexpr int K_PASSES = (kBN * KCH + NT - 1) / NT;
-    constexpr int V_TASKS = (kBN / 4) * (D / 4);     // 4 keys x 4 dims each
-    constexpr int V_PASSES = (V_TASKS + NT - 1) / NT;
-    constexpr int NKK = D / 16;                      // MFMA k-steps for QK^T
-    constexpr int NDB = D / 32;                      // 32-row blocks of O^T
+    constexpr int NKK = D / 16, NDB = D / 32;
+    constexpr int NLD = kBN / RPI / NWAVES;     // buffer_load..lds instructions per tile per wave
 
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t *Ks = smem;                       // [2][K_ELEMS]
-    uint16_t *Vs = smem + 2 * SM::K_ELEMS;     // [2][V_ELEMS]
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem_attn[];
+    uint8_t *Ks = smem_attn;                               // [3][kTileBytes], tile t in buffer t % 3
+    uint8_t *Vs = smem_attn + kAttnBufs * kTileBytes;   // [3][kTileBytes]
 
-    // ---- block -> (kv head g fastest, head-in-group, sequence, q tile heavy first)
     int bid = blockIdx.x;
     const int g = bid % p.Hkv;  bid /= p.Hkv;
     const int hg = bid % p.G;   bid /= p.G;
@@ -106,25 +177,31 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
     const int ks = min(p.cu_k[b], p.total_k), ke = min(p.cu_k[b + 1], p.total_k);
     const int nq = qe - qs, nk = ke - ks;
     const int m0 = t * BM;
-    if (m0 >= nq || nq <= 0) return;
+    const int tid = threadIdx.x;
+    // importance sweep: this workgroup's slice of the partial column sums, at its sequence
+    float *const part_row = IMP
+        ? p.imp_part + ((int64_t)(hg * p.n_qtiles + t) * p.Hkv + g) * p.total_k + ks : nullptr;
+    if (m0 >= nq || nq <= 0) {
+        if constexpr (IMP)   // no query rows here: the slice still has to read as zero
+            for (int j = tid; j < nk; j += NWAVES * 64) part_row[j] = 0.f;
+        return;
+    }
     const int delta = nk - nq;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hh = lane >> 5;
 
-    const int wave_q0 = m0 + 32 * wave;              // first query of this wave
+    const int wave_q0 = m0 + 32 * wave;
     const int qrow = wave_q0 + n;
     const int qrow_c = min(qrow, nq - 1);
-    const int lim = qrow_c + delta;                  // last visible key of this lane's query
+    const int lim = qrow_c + delta;
     const int wave_lim_max = min(wave_q0 + 31, nq - 1) + delta;
     const int wave_lim_min = min(wave_q0, nq - 1) + delta;
-
-    // keys needed by the workgroup: [0, kend)
     const int kend = min(nk, min(m0 + BM, nq) + delta);
     const int n_tiles = kend > 0 ? (kend + kBN - 1) / kBN : 0;
 
-    // ---- Q fragments (B operand): query n, dims 16*kk + 8*hh .. +7
+    // ---- Q fragments (B operand)
     bf16x8 qf[NKK];
     {
         const uint16_t *qp = p.q + (int64_t)(qs + qrow_c) * p.q_st + (int64_t)h * p.q_sh + 8 * hh;
@@ -132,178 +209,315 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
         for (int kk = 0; kk < NKK; ++kk) qf[kk] = *(const bf16x8 *)(qp + 16 * kk);
     }
 
+    // ---- buffer resources over this sequence's K / V rows of KV head g
     const uint16_t *kbase = p.k + (int64_t)ks * p.k_st + (int64_t)g * p.k_sh;
     const uint16_t *vbase = p.v + (int64_t)ks * p.v_st + (int64_t)g * p.v_sh;
+    const uint32_t k_row_bytes = (uint32_t)p.k_st * 2u, v_row_bytes = (uint32_t)p.v_st * 2u;
+    const uint32_t k_span = nk > 0 ? (uint32_t)(nk - 1) * k_row_bytes + (uint32_t)ROWB : 0u;
+    const uint32_t v_span = nk > 0 ? (uint32_t)(nk - 1) * v_row_bytes + (uint32_t)ROWB : 0u;
+    const uint32_t ks_lds = lds_addr_of(Ks), vs_lds = lds_addr_of(Vs);
 
-    u32x4 kreg[K_PASSES];
-    u32x2 vreg[V_PASSES][4];
-
-    auto load_tile = [&](int it) {
-        const int j0 = it * kBN;
+    // DMA lane mapping: instruction ci of wave w fills the RPI LDS rows RPI q .. RPI q + RPI - 1,
+    // q = w + NWAVES*ci; lane -> row RPI q + lane / CH, chunk position lane % CH, which holds
+    // chunk pos ^ swz(row).
+    uint32_t kvoff[NLD], vvoff[NLD];
 #pragma unroll
-        for (int ps = 0; ps < K_PASSES; ++ps) {
-            const int c = tid + ps * NT;
-            if (K_PASSES * NT == kBN * KCH || c < kBN * KCH) {
-                const int key = min(j0 + c / KCH, nk - 1);
-                kreg[ps] = *(const u32x4 *)(kbase + (int64_t)key * p.k_st + (c % KCH) * 8);
-            }
-        }
+    for (int ci = 0; ci < NLD; ++ci) {
+        const int r = RPI * (wave + NWAVES * ci) + lane / CH;
+        const int c = (lane % CH) ^ swz_row<D>(r);
+        kvoff[ci] = (uint32_t)r * k_row_bytes + (uint32_t)c * 16u;
+        vvoff[ci] = (uint32_t)r * v_row_bytes + (uint32_t)c * 16u;
+    }
+    // The tile's offset goes into the descriptor (scalar arithmetic): base advanced by the tile,
+    // num_records reduced by the same amount, so that the range check still ends at the sequence's
+    // last row and the per-lane offsets stay constant.
+    auto tile_rsrc = [&](const uint16_t *base, uint32_t span, uint32_t so) {
+        // span - min(so, span) on the scalar unit (the compiler turns the C form into a saturating
+        // subtract, which exists only on the vector unit and then needs a readfirstlane)
+        uint32_t left;
+        asm("s_min_u32 %0, %1, %2\n\ts_sub_u32 %0, %2, %0" : "=&s"(left) : "s"(so), "s"(span) : "scc");
+        return make_rsrc((const uint8_t *)base + so, left);
+    };
+    auto issue_k = [&](int tile, int buf) {
+        const i32x4 rs = tile_rsrc(kbase, k_span, (uint32_t)tile * kBN * k_row_bytes);
 #pragma unroll
-        for (int ps = 0; ps < V_PASSES; ++ps) {
-            const int task = tid + ps * NT;
-            if (V_PASSES * NT == V_TASKS || task < V_TASKS) {
-                const int dg = task % (D / 4), kg = task / (D / 4);
+        for (int ci = 0; ci < NLD; ++ci)
+            dma16_to_lds(rs, ks_lds + buf * kTileBytes + 1024 * (wave + NWAVES * ci), kvoff[ci]);
+    };
+    auto issue_v = [&](int tile, int buf) {
+        const i32x4 rs = tile_rsrc(vbase, v_span, (uint32_t)tile * kBN * v_row_bytes);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int key = min(j0 + 4 * kg + i, nk - 1);
-                    vreg[ps][i] = *(const u32x2 *)(vbase + (int64_t)key * p.v_st + 4 * dg);
-                }
-            }
-        }
+        for (int ci = 0; ci < NLD; ++ci)
+            dma16_to_lds(rs, vs_lds + buf * kTileBytes + 1024 * (wave + NWAVES * ci), vvoff[ci]);
     };
 
-    auto store_tile = [&](int buf) {
-        uint16_t *Kb = Ks + buf * SM::K_ELEMS;
-        uint16_t *Vb = Vs + buf * SM::V_ELEMS;
+    // ---- LDS read addresses (bytes inside a tile)
+    // K fragment (A operand of S^T): row n (+32 for the second block), chunk (2kk+hh) ^ swz(n)
+    uint32_t kaddr[NKK];
 #pragma unroll
-        for (int ps = 0; ps < K_PASSES; ++ps) {
-            const int c = tid + ps * NT;
-            if (K_PASSES * NT == kBN * KCH || c < kBN * KCH)
-                *(u32x4 *)(Kb + (c / KCH) * SM::KSTR + (c % KCH) * 8) = kreg[ps];
-        }
+    for (int kk = 0; kk < NKK; ++kk) kaddr[kk] = (uint32_t)(n * ROWB + ((2 * kk + hh) ^ swz_row<D>(n)) * 16);
+    // V^T fragment (A operand of O^T) through the transposing read: the 16 lanes of group
+    // gamma = lane/16 address 4 keys x 16 dims; source lane s reads key (s>>2), dims 4(s&3)..+3.
+    // Keys of step st, half hh, read eg: 16 st + 8 eg + 4 hh + (s>>2).
+    uint32_t vaddr[NDB][2];
+    {
+        const int s16 = lane & 15, dhalf = (lane >> 4) & 1;
 #pragma unroll
-        for (int ps = 0; ps < V_PASSES; ++ps) {
-            const int task = tid + ps * NT;
-            if (V_PASSES * NT == V_TASKS || task < V_TASKS) {
-                const int dg = task % (D / 4), kg = task / (D / 4);
-                // quad of 4 keys -> slot inside its 16-key group: (0,1,2,3) -> (0,2,1,3)
-                const int qd = kg & 3;
-                const int slot = 16 * (kg >> 2) + 4 * (((qd & 1) << 1) | (qd >> 1));
-                const u32x2 r0 = vreg[ps][0], r1 = vreg[ps][1], r2 = vreg[ps][2], r3 = vreg[ps][3];
-                // 4x4 transpose of 16-bit values: row = key, column = dim
-                u32x2 c0, c1, c2, c3;
-                c0.x = (r0.x & 0xffffu) | (r1.x << 16);  c0.y = (r2.x & 0xffffu) | (r3.x << 16);
-                c1.x = (r0.x >> 16) | (r1.x & 0xffff0000u);  c1.y = (r2.x >> 16) | (r3.x & 0xffff0000u);
-                c2.x = (r0.y & 0xffffu) | (r1.y << 16);  c2.y = (r2.y & 0xffffu) | (r3.y << 16);
-                c3.x = (r0.y >> 16) | (r1.y & 0xffff0000u);  c3.y = (r2.y >> 16) | (r3.y & 0xffff0000u);
-                uint16_t *dst = Vb + (4 * dg) * SM::VSTR + slot;
-                *(u32x2 *)(dst) = c0;
-                *(u32x2 *)(dst + SM::VSTR) = c1;
-                *(u32x2 *)(dst + 2 * SM::VSTR) = c2;
-                *(u32x2 *)(dst + 3 * SM::VSTR) = c3;
+        for (int eg = 0; eg < 2; ++eg) {
+            const int row = 8 * eg + 4 * hh + (s16 >> 2);          // + 16 st
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                const int chunk = 4 * db + 2 * dhalf + ((s16 & 3) >> 1);
+                vaddr[db][eg] = vs_lds + (uint32_t)(row * ROWB + (chunk ^ swz_row<D>(row)) * 16) + 8u * (s16 & 1);
             }
         }
-    };
+    }
 
     f32x16 oacc[NDB];
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
-    float m_run = -INFINITY;   // running max of raw (unscaled) scores, shared by both halves
-    float l_run = 0.f;         // this half's partial row sum
+    // Online-softmax state of this lane's query, kept in the log2 domain: every score enters as
+    //   t = s * c2 + ref      (c2 = softmax scale * log2 e, ref = minus the row's reference exponent)
+    // and contributes 2^t.  The reference only has to keep 2^t in range, it need not be the
+    // running max: it is set by the first block that holds a visible key and renewed when a
+    // block's largest t exceeds kLazyLog2 (probabilities relative to it stay below 2^kLazyLog2,
+    // far inside the range of fp32 sums and bf16 operands), so O and the row sums are rescaled a
+    // few times per row instead of whenever a max moves.
+    float l_part[4] = {0.f, 0.f, 0.f, 0.f};   // four interleaved partial row sums (short add chains)
     const float c2 = p.scale_log2;
+    float ref = 0.f;                           // 0 until the row has a reference
+    float thr = -INFINITY;                     // a block max above it renews the reference: -inf, then kLazyLog2
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // S^T of the 32-key block at byte offset `koff` of the K buffers
+    auto qk_block = [&](uint32_t koff, f32x16 &s) {
+        const uint8_t *kb = Ks + koff;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+            const bf16x8 a = *(const bf16x8 *)(kb + kaddr[kk]);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], kk == 0 ? zero16 : s, 0, 0, 0);
+        }
+    };
+
+    // t = s * c2 + ref in place
+    auto to_log2 = [&](f32x16 &s) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[e] = fmaf(s[e], c2, ref);
+    };
+
+    // largest entry of the query's row in this block; its keys are spread over this lane and
+    // lane ^ 32.  Short dependency chains: a 3-level tree of v_max3 instead of one serial chain.
+    auto row_max = [&](const f32x16 &s) {
+        const float t0 = max3(s[0], s[1], s[2]), t1 = max3(s[4], s[5], s[6]);
+        const float t2 = max3(s[8], s[9], s[10]), t3 = max3(s[12], s[13], s[14]);
+        const float u0 = max3(t0, t1, s[3]), u1 = max3(t2, t3, s[7]);
+        const float tmax = max3(max3(u0, u1, s[11]), s[15], s[15]);
+        const uint32_t u = __float_as_uint(tmax);
+        const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    };
+
+    // Rare and wave-uniform: the rows whose block max t_max exceeds their threshold take it as
+    // their new reference; O, the row sums and the block `blk` (already in the log2 domain) move
+    // with it.  Rows without a reference (thr = -inf, nothing accumulated yet) get their first
+    // one the same way; a block in which a row sees no key (t_max = -inf) changes nothing.
+    auto renew = [&](float t_max, f32x16 &blk) {
+        const bool up = t_max > thr;
+        const float shift = up ? t_max : 0.f;
+        const float alpha = fast_exp2(-shift);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) l_part[i] *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) blk[e] -= shift;
+        ref -= shift;
+        thr = up ? kLazyLog2 : thr;
+    };
+
+    // a block in the log2 domain -> probabilities relative to the reference, added to the row sums
+    auto exp_block = [&](f32x16 &s) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            s[e] = fast_exp2(s[e]);
+            l_part[e & 3] += s[e];
+        }
+    };
+
+    // O^T += V^T P^T for the 32-key block at byte offset `voff` of the V buffers
+    auto pv_block = [&](uint32_t voff, const f32x16 &s) {
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            f32x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = s[8 * st + e];
+            const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                const bf16x8 a = lds_read_tr8(vaddr[db][0] + voff + 16 * ROWB * st, vaddr[db][1] + voff + 16 * ROWB * st);
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
+            }
+        }
+    };
 
     if (n_tiles > 0) {
-        load_tile(0);
-        store_tile(0);
+        issue_k(0, 0);
+        issue_v(0, 0);
+        if (n_tiles > 1) issue_k(1, 1);
     }
-    __syncthreads();
-    // Everything loaded so far (Q fragments included) has landed: say so, or the
-    // compiler re-waits for the Q loads inside the loop, behind the prefetches.
     __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
 
-    for (int it = 0; it < n_tiles; ++it) {
-        const int buf = it & 1;
-        const int j0 = it * kBN;
-        const bool more = it + 1 < n_tiles;
-        if (more) load_tile(it + 1);
+    // Scores are pipelined per 32-key block u = 2*tile + blk: while block u goes
+    // through softmax and PV, the MFMAs of block u+1 are already issued.  Tile t
+    // lives in LDS buffer t % 3; at every tile boundary the current block is in sA.
+    const int n_blocks = 2 * n_tiles;
+    f32x16 sA = zero16, sB = zero16;
+    if (n_tiles > 0) qk_block(0, sA);   // block 0 is visible to every wave
 
-        if (j0 <= wave_lim_max) {   // wave-uniform: some query of this wave sees this tile
-            const uint16_t *Kb = Ks + buf * SM::K_ELEMS;
-            const uint16_t *Vb = Vs + buf * SM::V_ELEMS;
-            const bool blk1 = (j0 + 32 <= wave_lim_max);   // second 32-key block visible?
+    // ---- hot loop: tiles that no wave of the workgroup has to mask (fully visible to the
+    // workgroup's first query: 64 (t+1) - 1 <= m0 + delta) and that have a successor tile: no
+    // per-wave branches at all.  The scores the last hot tile computes ahead for the first
+    // block of the next (diagonal) tile are masked by the generic loop before they are used.
+    const int first_lim = m0 + delta;
+    const int n_hot = max(0, min((first_lim + 1) / kBN, n_tiles - 1));   // tiles 0 .. n_hot-1
 
-            f32x16 s0, s1;
+    // The block `cur` arrives in the log2 domain (see above): the scale-and-shift and the row max
+    // of a block are done one phase before its exponentials, while the previous PV MFMAs run, so
+    // that the exponentials never wait for a max.  LDS fragment reads are issued a phase ahead of
+    // the MFMAs that consume them: the V^T fragments of `cur` before the QK MFMAs of `nxt`, the K
+    // fragments of the block after `nxt` (`kf`) before the PV MFMAs of `cur`.
+    bf16x8 kf[NKK];
+    auto load_kf = [&](uint32_t koff) {
+        const uint8_t *kb = Ks + koff;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) { s0[e] = 0.f; s1[e] = 0.f; }
-            {
-                const uint16_t *ka = Kb + n * SM::KSTR + 8 * hh;
+        for (int kk = 0; kk < NKK; ++kk) kf[kk] = *(const bf16x8 *)(kb + kaddr[kk]);
+    };
+    // The wave runs at raised issue priority while it has the exponentials to do and at normal
+    // priority during its PV MFMAs (measured: 1 % on the 32k prompt, 3 % on constant inputs).
+    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, uint32_t k_next2, uint32_t v_cur) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_setprio(1);
+        bf16x8 vf[2][NDB];
 #pragma unroll
-                for (int kk = 0; kk < NKK; ++kk) {
-                    const bf16x8 a = *(const bf16x8 *)(ka + 16 * kk);
-                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s0, 0, 0, 0);
-                }
-                if (blk1) {
+        for (int st = 0; st < 2; ++st)
 #pragma unroll
-                    for (int kk = 0; kk < NKK; ++kk) {
-                        const bf16x8 a = *(const bf16x8 *)(ka + 32 * SM::KSTR + 16 * kk);
-                        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s1, 0, 0, 0);
-                    }
-                }
-            }
-            // ---- causal / length mask (only tiles that touch the diagonal)
-            if (j0 + kBN - 1 > wave_lim_min) {
+            for (int db = 0; db < NDB; ++db)
+                vf[st][db] = lds_read_tr8(vaddr[db][0] + v_cur + 16 * ROWB * st, vaddr[db][1] + v_cur + 16 * ROWB * st);
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+            nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], kk == 0 ? zero16 : nxt, 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cur[e] = fast_exp2(cur[e]);   // cur is in the log2 domain
+        bf16x8 pb[2];
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            f32x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = cur[8 * st + e];
+            pb[st] = __builtin_convertvector(pf, bf16x8);
+        }
+        // Issue order of this phase, pinned: after every QK MFMA two exponentials, two V^T
+        // fragment reads and one bf16 pack.  Left to itself the compiler bunches the exponentials
+        // behind the first MFMAs and the reads behind the middle ones, and the two waves of a SIMD
+        // then queue for the same unit (measured: 10 % fewer cycles on constant inputs, 2.5 % less
+        // time on the 32k prompt, where the clock gives way as the matrix pipe fills).
+#pragma unroll
+        for (int i = 0; i < NKK; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x400, 16 / NKK, 0);   // transcendental
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);          // 2 DS reads
+            __builtin_amdgcn_sched_group_barrier(0x002, 8 / NKK, 0);    // VALU (bf16 packs)
+        }
+        __builtin_amdgcn_s_setprio(0);
+        load_kf(k_next2);
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            const bf16x8 pbs = pb[st];
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pbs, oacc[db], 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) l_part[e & 3] += cur[e];      // row sums: also in this phase
+        // The next block enters the log2 domain here, in the phase whose VALU is otherwise idle,
+        // against the present reference (nothing here depends on the check below, so all of it can
+        // be issued between the PV MFMAs).
+        to_log2(nxt);
+        const float t_max = row_max(nxt);
+        // same for this phase: after every PV MFMA one K fragment read and five of the additions,
+        // multiply-adds and max operations above
+#pragma unroll
+        for (int i = 0; i < 2 * NDB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              // 1 DS read
+            __builtin_amdgcn_sched_group_barrier(0x002, 40 / (2 * NDB), 0); // VALU
+        }
+        if (__any(t_max > thr)) renew(t_max, nxt);
+    };
+    auto hot_tile = [&](auto par_c, const int it) {
+        constexpr int PAR = decltype(par_c)::value;
+        constexpr int P1 = (PAR + 1) % 3, P2 = (PAR + 2) % 3;
+        issue_v(it + 1, P1);
+        if (it + 2 < n_tiles) issue_k(it + 2, P2);
+        hot_half(sA, sB, P1 * kTileBytes, PAR * kTileBytes);
+        hot_half(sB, sA, P1 * kTileBytes + 32 * ROWB, PAR * kTileBytes + 32 * ROWB);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
+    int it = 0;
+    if (n_hot > 0) {
+        to_log2(sA);                                // the first block sets every row's reference
+        renew(row_max(sA), sA);
+        load_kf(32 * ROWB);
+        for (; it + 3 <= n_hot; it += 3) {          // unrolled over the three LDS buffers
+            hot_tile(std::integral_constant<int, 0>{}, it);
+            hot_tile(std::integral_constant<int, 1>{}, it + 1);
+            hot_tile(std::integral_constant<int, 2>{}, it + 2);
+        }
+        if (it < n_hot) { hot_tile(std::integral_constant<int, 0>{}, it); ++it; }
+        if (it < n_hot) { hot_tile(std::integral_constant<int, 1>{}, it); ++it; }
+        // the hot loop leaves sA scaled and shifted; the generic loop wants the raw scores of its
+        // first block (one extra QK block per workgroup)
+        qk_block((uint32_t)(it % 3) * kTileBytes, sA);
+    }
+
+    // ---- remaining tiles (the diagonal region): per-wave activity and masking
+    auto slow_half = [&](f32x16 &cur, f32x16 &nxt, const int u, uint32_t k_next, uint32_t v_cur) {
+        const int j0 = 32 * u;
+        const bool cur_active = j0 <= wave_lim_max;
+        const bool nxt_active = u + 1 < n_blocks && j0 + 32 <= wave_lim_max;
+        if (nxt_active) qk_block(k_next, nxt);
+        if (cur_active) {
+            if (j0 + 31 > wave_lim_min) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int j = j0 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    if (j > lim) s0[e] = -INFINITY;
-                    if (j + 32 > lim) s1[e] = -INFINITY;
+                    if (j > lim) cur[e] = -INFINITY;
                 }
             }
-            // ---- online softmax
-            float tmax = max3(s0[0], s0[1], s0[2]);
-#pragma unroll
-            for (int e = 3; e < 15; e += 2) tmax = max3(tmax, s0[e], s0[e + 1]);
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) tmax = max3(tmax, s1[e], s1[e + 1]);
-            tmax = max3(tmax, s0[15], xchg_half(max3(tmax, s0[15], s0[15])));
-            const float m_new = fmaxf(m_run, tmax);
-            if (__any(m_new > m_run)) {           // wave-uniform: rescale only when a max moved
-                const float alpha = (m_run == -INFINITY) ? 0.f : fast_exp2((m_run - m_new) * c2);
-                l_run *= alpha;
-#pragma unroll
-                for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-                m_run = m_new;
-            }
-            const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
-            float psum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                s0[e] = fast_exp2(fmaf(s0[e], c2, -mc));
-                psum += s0[e];
-            }
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                s1[e] = fast_exp2(fmaf(s1[e], c2, -mc));
-                psum += s1[e];
-            }
-            l_run += psum;
-
-            // ---- O^T += V^T P^T ; 16 keys per step, B operand straight from s0/s1
-            const uint16_t *va = Vb + n * SM::VSTR + 8 * hh;
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                if (st >= 2 && !blk1) break;
-                f32x8 pf;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = (st < 2) ? s0[8 * (st & 1) + e] : s1[8 * (st & 1) + e];
-                const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
-#pragma unroll
-                for (int db = 0; db < NDB; ++db) {
-                    const bf16x8 a = *(const bf16x8 *)(va + (32 * db) * SM::VSTR + 16 * st);
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
-                }
-            }
+            to_log2(cur);                         // masked entries stay -inf
+            const float t_max = row_max(cur);
+            if (__any(t_max > thr)) renew(t_max, cur);
+            exp_block(cur);
+            pv_block(v_cur, cur);
         }
-
-        if (more) store_tile(buf ^ 1);
+    };
+    for (; it < n_tiles; ++it) {
+        const uint32_t b0 = (uint32_t)(it % 3) * kTileBytes, b1 = (uint32_t)((it + 1) % 3) * kTileBytes;
+        if (it + 1 < n_tiles) issue_v(it + 1, (it + 1) % 3);
+        if (it + 2 < n_tiles) issue_k(it + 2, (it + 2) % 3);
+        slow_half(sA, sB, 2 * it, b0 + 32 * ROWB, b0);
+        slow_half(sB, sA, 2 * it + 1, b1, b0 + 32 * ROWB);
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
 
-    // ---- epilogue: normalise, write O (bf16) and LSE (fp32, natural log)
+    // ---- epilogue
+    const float l_run = (l_part[0] + l_part[1]) + (l_part[2] + l_part[3]);
     const float l_tot = l_run + xchg_half(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (qrow < nq) {
@@ -321,11 +535,174 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
         }
         if (hh == 0) {
             const float lse = l_tot > 0.f
-                ? (m_run * c2 + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f
+                ? (__builtin_amdgcn_logf(l_tot) - ref) * 0.6931471805599453f
                 : -INFINITY;
             p.lse[(int64_t)h * p.total_q + qs + qrow] = lse;
         }
     }
+
+    // ---- importance sweep (paper Section 3.2, token importance of an observation window that
+    // covers every query of the call): with the final log-sum-exp of its 32 rows in hand, each
+    // wave walks the same K tiles again, recomputes S = Q K^T with the operands exchanged (lane =
+    // key, registers = the wave's 32 query rows), turns it into the normalised probabilities and
+    // adds them up along the query dimension.  The eight waves' column sums of a 64-key tile meet
+    // in LDS; one wave adds them in the fixed order wave 0, 1, ... and writes the tile's 64 sums.
+    // No atomics: the result does not depend on timing.
+    if constexpr (IMP) {
+        // LDS: K tiles now rotate through kSweepBufs buffers (the K and V buffers of the first
+        // sweep, contiguous); the log-sum-exp exchange and the column sums lie behind them.  A step
+        // is short (16 MFMAs per wave), so a tile is requested five steps before its first use and
+        // the wait at the end of a step leaves the two youngest requests in flight.
+        float *lse_sh = (float *)(smem_attn + kSweepBufs * kTileBytes);          // [NWAVES][32]
+        float *red = (float *)(smem_attn + kSweepBufs * kTileBytes + 1024);      // [2][64][NWAVES]
+        // a row's probabilities are 2^(s * c2 - lse2); rows past the end or without a visible key give 0
+        const float lse2 = (qrow < nq && l_tot > 0.f) ? __builtin_amdgcn_logf(l_tot) - ref : INFINITY;
+        if (hh == 0) lse_sh[wave * 32 + n] = lse2;
+        for (int tl = 0; tl < kSweepAhead; ++tl) issue_k(tl, tl);   // tiles past the end read as zero
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        float nl[16];                              // minus lse2 of the rows this lane's registers hold
+#pragma unroll
+        for (int bq = 0; bq < 4; ++bq) {
+            const f32x4 x = *(const f32x4 *)(lse_sh + wave * 32 + 8 * bq + 4 * hh);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) nl[4 * bq + r] = -x[r];
+        }
+        // S of the 32-key block at byte offset `koff`: rows 8 (e / 4) + 4 hh + e % 4 of the wave, key n
+        auto qk_rows = [&](uint32_t koff, f32x16 &s) {
+            const uint8_t *kb = Ks + koff;
+#pragma unroll
+            for (int kk = 0; kk < NKK; ++kk) {
+                const bf16x8 kfrag = *(const bf16x8 *)(kb + kaddr[kk]);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], kfrag, kk == 0 ? zero16 : s, 0, 0, 0);
+            }
+        };
+        // this lane's share (16 of the wave's 32 rows) of the probabilities of key j0 + n
+        auto half_sum = [&](const float (&c)[4]) { return (c[0] + c[1]) + (c[2] + c[3]); };
+        auto col_sum = [&](const f32x16 &s, const int j0) {
+            float c[4] = {0.f, 0.f, 0.f, 0.f};
+            if (j0 + 31 > wave_lim_min) {          // the block touches the diagonal (or the end of K)
+                const int jj = j0 + n - delta - wave_q0 - 4 * hh;   // visible to row r iff jj <= r - 4 hh
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float pe = fast_exp2(fmaf(s[e], c2, nl[e]));
+                    c[e & 3] += (jj <= 8 * (e >> 2) + (e & 3)) ? pe : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) c[e & 3] += fast_exp2(fmaf(s[e], c2, nl[e]));
+            }
+            return half_sum(c);
+        };
+        // x0 / x1: the lane's shares for the tile's first / second 32-key block.  One half-wave swap
+        // completes both sums at once: afterwards lane l holds the wave's column sum of key l of
+        // the tile.  The waves' sums meet in LDS as red[tile parity][key][wave]; after the barrier
+        // (which also publishes a K tile) wave it2 % NWAVES adds the NWAVES values of each key in
+        // the fixed order wave 0, 1, ... and stores the tile's 64 sums.
+        auto tile_done = [&](const int it2, const float x0, const float x1) {
+            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x0), __float_as_uint(x1), false, false);
+            red[(((it2 & 1) * 64 + lane) * NWAVES) + wave] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+            // every step requests one tile (NLD loads per wave): all but the two youngest requests
+            // have landed, i.e. the tiles up to it2 + 3; a store of the summing wave in between
+            // only makes the wait stricter
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(2 * NLD) : "memory");
+            __syncthreads();
+            if (wave == it2 % NWAVES) {
+                f32x4 v[NWAVES / 4];
+#pragma unroll
+                for (int q = 0; q < NWAVES / 4; ++q)
+                    v[q] = *(const f32x4 *)(red + (((it2 & 1) * 64 + lane) * NWAVES) + 4 * q);
+                float acc = v[0][0];
+#pragma unroll
+                for (int w = 1; w < NWAVES; ++w) acc += v[w / 4][w % 4];
+                const int j = 64 * it2 + lane;
+                if (j < nk) part_row[j] = acc;
+            }
+        };
+        // At the top of step it2 the scores of tile it2 are in registers, tiles it2+1 and it2+2 are
+        // in LDS (tile t in buffer t % kSweepBufs) and tiles it2+3, it2+4 are requested.
+        f32x16 sa[2] = {zero16, zero16}, sb[2] = {zero16, zero16};
+        if (n_tiles > 0) {
+            qk_rows(0, sa[0]);
+            qk_rows(32 * ROWB, sa[1]);
+        }
+        int it2 = 0;
+        // Tiles every row of the workgroup sees in full and that have a successor (the same ones as
+        // in the first sweep): no masks.  While the probabilities of tile it2 are summed, the 16
+        // MFMAs of tile it2+1 are issued, alternating between its two 32-key blocks so that
+        // consecutive MFMAs are independent; each K fragment is read four MFMAs before its use.
+        bf16x8 fr[4];
+        auto frag_at = [&](uint32_t tile_off, int i) {
+            return *(const bf16x8 *)(Ks + tile_off + (i & 1) * 32 * ROWB + kaddr[i >> 1]);
+        };
+        auto sweep_step = [&](auto par_c, const f32x16 (&sc)[2], f32x16 (&sn)[2]) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(par_c)::value;      // it2 % kSweepBufs
+            constexpr uint32_t T1 = (uint32_t)((PAR + 1) % kSweepBufs) * kTileBytes;
+            constexpr uint32_t T2 = (uint32_t)((PAR + 2) % kSweepBufs) * kTileBytes;
+            issue_k(it2 + kSweepAhead, (PAR + kSweepAhead) % kSweepBufs);
+            constexpr int NM = 2 * NKK;                      // MFMAs of a tile
+            constexpr int EP = 32 / NM;                      // probabilities summed per MFMA
+            float c[2][4];
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                const int blk = i & 1, kk = i >> 1;
+                sn[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], fr[i & 3], kk == 0 ? zero16 : sn[blk], 0, 0, 0);
+                fr[i & 3] = i + 4 < NM ? frag_at(T1, i + 4) : frag_at(T2, i + 4 - NM);
+#pragma unroll
+                for (int x = 0; x < EP; ++x) {
+                    const int cb = i / NKK, e = EP * (i % NKK) + x;
+                    const float pe = fast_exp2(fmaf(sc[cb][e], c2, nl[e]));
+                    c[cb][e & 3] = e < 4 ? pe : c[cb][e & 3] + pe;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // 1 DS read
+                __builtin_amdgcn_sched_group_barrier(0x002, EP, 0);   // multiply-adds
+                __builtin_amdgcn_sched_group_barrier(0x400, EP, 0);   // transcendental
+                __builtin_amdgcn_sched_group_barrier(0x002, EP, 0);   // additions
+            }
+            tile_done(it2, half_sum(c[0]), half_sum(c[1]));
+            ++it2;
+        };
+        if (n_hot > 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fr[i] = frag_at(kTileBytes, i);
+            while (it2 + 6 <= n_hot) {
+                sweep_step(std::integral_constant<int, 0>{}, sa, sb);
+                sweep_step(std::integral_constant<int, 1>{}, sb, sa);
+                sweep_step(std::integral_constant<int, 2>{}, sa, sb);
+                sweep_step(std::integral_constant<int, 3>{}, sb, sa);
+                sweep_step(std::integral_constant<int, 4>{}, sa, sb);
+                sweep_step(std::integral_constant<int, 5>{}, sb, sa);
+            }
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 0>{}, sa, sb);
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 1>{}, sb, sa);
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 2>{}, sa, sb);
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 3>{}, sb, sa);
+            if (it2 < n_hot) sweep_step(std::integral_constant<int, 4>{}, sa, sb);
+            if (n_hot & 1) { sa[0] = sb[0]; sa[1] = sb[1]; }
+        }
+        // the diagonal region; sa holds the scores of its first tile
+        for (; it2 < n_tiles; ++it2) {
+            issue_k(it2 + kSweepAhead, (it2 + kSweepAhead) % kSweepBufs);
+            const float c0 = col_sum(sa[0], 64 * it2);
+            const float c1 = col_sum(sa[1], 64 * it2 + 32);
+            tile_done(it2, c0, c1);
+            if (it2 + 1 < n_tiles) {
+                const uint32_t b1 = (uint32_t)((it2 + 1) % kSweepBufs) * kTileBytes;
+                qk_rows(b1, sa[0]);
+                qk_rows(b1 + 32 * ROWB, sa[1]);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);   // requests past the last tile are still in flight
+        // keys that no query of this tile can see
+        for (int j = 64 * n_tiles + tid; j < nk; j += NWAVES * 64) part_row[j] = 0.f;
+    }
+#else
+    (void)p;
+#endif
 }
 
 }  // namespace pdd

@@ -20,7 +20,7 @@
 // registers, so the sum over queries is in-lane; no atomics, fixed summation
 // order, deterministic.
 #pragma once
-#include "attn_fwd_d128.hpp"
+#include "attn_fwd.hpp"
 
 namespace pdd {
 
@@ -134,7 +134,7 @@ void importance_kernel(const ImpParams p)
         for (int ci = 0; ci < NLD; ++ci) {
             const int flat = (wave + kImpWaves * ci) * 64 + lane;          // 16-byte slot in the block
             const int r = flat / CH, pos = flat % CH;
-            const int c = D == 128 ? (pos ^ swz16(r)) : (pos ^ ((r >> 1) & 7));
+            const int c = D == 128 ? (pos ^ swz_row<128>(r)) : (pos ^ ((r >> 1) & 7));
             qrow_l[ci] = r;
             qvoff[ci] = (uint32_t)c * 16u;
         }
@@ -157,7 +157,7 @@ void importance_kernel(const ImpParams p)
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
             const int c = 2 * kk + hh;
-            const int cs = D == 128 ? (c ^ swz16(n)) : (c ^ ((n >> 1) & 7));
+            const int cs = D == 128 ? (c ^ swz_row<128>(n)) : (c ^ ((n >> 1) & 7));
             qaddr[kk] = (uint32_t)n * ROW_BYTES + (uint32_t)cs * 16u;
         }
 

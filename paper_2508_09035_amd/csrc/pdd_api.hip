@@ -11,7 +11,6 @@
 #include <cstring>
 
 #include "attn_fwd.hpp"
-#include "attn_fwd_d128.hpp"
 #include "importance.hpp"
 #include "select_topk.hpp"
 #include "pack_mask.hpp"
@@ -140,12 +139,9 @@ pdd_status launch_attn_kernel(Kern kern, int smem, int threads, const pdd::AttnP
 template <int D, int NW>
 pdd_status launch_attn_t(const pdd::AttnParams &p, int64_t blocks, hipStream_t st)
 {
-    if constexpr (D == 128) {
-        if (p.imp_part)
-            return launch_attn_kernel(pdd::attn_fwd_d128_kernel<NW, true>, pdd::kAttn128SweepSmem, NW * 64, p, blocks, st);
-        return launch_attn_kernel(pdd::attn_fwd_d128_kernel<NW>, pdd::kAttn128Smem, NW * 64, p, blocks, st);
-    } else
-        return launch_attn_kernel(pdd::attn_fwd_kernel<D, NW>, pdd::AttnSmem<D>::BYTES, NW * 64, p, blocks, st);
+    if (p.imp_part)
+        return launch_attn_kernel(pdd::attn_fwd_kernel<D, NW, true>, pdd::AttnSmem<D>::SWEEP_BYTES, NW * 64, p, blocks, st);
+    return launch_attn_kernel(pdd::attn_fwd_kernel<D, NW>, pdd::AttnSmem<D>::BYTES, NW * 64, p, blocks, st);
 }
 
 // Queries per attention workgroup: 8 waves (256 queries) halve the K/V traffic per flop; they
@@ -159,13 +155,13 @@ int attn_rows_per_workgroup(const pdd_attn_desc *d)
     return nw * 32;
 }
 
-// Chunked mode with head_dim 128 can take the token importance from a second sweep inside the
+// Chunked mode can take the token importance from a second sweep inside the
 // attention kernel (every query of the call is a window query there).  Its partial sums need one
 // float per (query head, query tile, key); 0 = this shape does not use the sweep.
 constexpr size_t kSweepWorkspaceMax = (size_t)256 << 20;
 size_t sweep_workspace(const pdd_attn_desc *d)
 {
-    if (d->head_dim != 128 || d->total_q == 0 || d->total_k == 0) return 0;
+    if (d->total_q == 0 || d->total_k == 0) return 0;
     const int bm = attn_rows_per_workgroup(d);
     const size_t n_qtiles = (size_t)((d->max_seqlen_q + bm - 1) / bm);
     const size_t need = n_qtiles * d->n_q_heads * (size_t)d->total_k * sizeof(float);
@@ -178,7 +174,7 @@ void launch_importance_reduce(const float *part, float *imp, int64_t n, int n_sp
                        part, imp, n, n_split);
 }
 
-// imp_part != NULL: head_dim 128 only, sweep_workspace(d) bytes; the importance sweep runs inside
+// imp_part != NULL: sweep_workspace(d) bytes; the importance sweep runs inside
 // the attention kernel and leaves its partial sums there.
 pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, const void *v, void *o, float *lse,
                        hipStream_t st, float *imp_part = nullptr)
@@ -202,14 +198,14 @@ pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, con
     p.n_qtiles = (d->max_seqlen_q + bm - 1) / bm;
     const int64_t blocks = (int64_t)p.n_qtiles * d->batch * d->n_q_heads;
     if (blocks > 0x7fffffffLL) return fail(PDD_ERR_INVALID_ARG, "launch grid too large");
-    if (d->head_dim == 128) {
-        // 32-bit byte offsets inside one sequence's K / V span (buffer addressing)
-        // (the kernels request up to six tiles of 64 rows past a sequence's end, which read as zero)
+    {   // 32-bit byte offsets inside one sequence's K / V span (buffer addressing); the kernels
+        // request up to six tiles of 64 rows past a sequence's end, which read as zero
         const int64_t span = ((int64_t)d->max_seqlen_k + 512) * 2 *
                              (d->k_stride_tok > d->v_stride_tok ? d->k_stride_tok : d->v_stride_tok);
         if (span >= (1LL << 32)) return fail(PDD_ERR_UNSUPPORTED, "a sequence's K/V span must stay below 4 GiB");
-        return nw == 8 ? launch_attn_t<128, 8>(p, blocks, st) : launch_attn_t<128, 4>(p, blocks, st);
     }
+    if (d->head_dim == 128)
+        return nw == 8 ? launch_attn_t<128, 8>(p, blocks, st) : launch_attn_t<128, 4>(p, blocks, st);
     return nw == 8 ? launch_attn_t<64, 8>(p, blocks, st) : launch_attn_t<64, 4>(p, blocks, st);
 }
 
