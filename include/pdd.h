@@ -118,7 +118,7 @@ enum {
  * Requires Nq_b == Nk_b for every sequence when host copies are given (use the
  * chunked entry point otherwise).
  * Limits (PDD_ERR_UNSUPPORTED beyond them; the kernels address with 32-bit byte
- * offsets): for head_dim 128 the K and V rows of one sequence,
+ * offsets): the K and V rows of one sequence,
  * (max_seqlen_k + 512) * stride_tok * 2 bytes, must span less than 4 GiB; with
  * an importance output the same holds for one sequence's Q rows and for the
  * whole lse tensor (Hq * total_q * 4 bytes).
@@ -135,16 +135,15 @@ pdd_status pdd_prefill_attn(const pdd_attn_desc *desc, const void *q, const void
  * remaining chunk catches up afterwards).  Same formulas as above with
  * delta_b = Nk_b - Nq_b >= 0.  Every chunk query is a window query
  * (desc->window is ignored) when importance is non-NULL.
- * workspace: as for pdd_prefill_attn, with one more form for head_dim 128.
+ * workspace: as for pdd_prefill_attn, with one more form.
  * Given pdd_workspace_bytes(desc, PDD_CALL_PREFILL_ATTN_CHUNKED) bytes (one
  * float per query head, tile of 128 or 256 queries and key), the importance is
  * taken inside the attention kernel: once a workgroup knows the log-sum-exp of
  * its queries it walks its K tiles a second time, with Q still in registers,
  * and leaves the column sums of its probabilities in the workspace; a short
  * second kernel adds them over the heads of a group and the query tiles in a
- * fixed order.  Shapes that would need more than 256 MiB for this, head_dim 64
- * and calls that are given less use the separate importance kernel described
- * above.  All forms are deterministic and agree to fp32 rounding.
+ * fixed order.  Shapes that would need more than 256 MiB for this and calls
+ * that are given less use the separate importance kernel described above.  All forms are deterministic and agree to fp32 rounding.
  */
 pdd_status pdd_prefill_attn_chunked(const pdd_attn_desc *desc, const void *q_chunk,
                                     const void *k_all, const void *v_all, void *o, float *lse,
@@ -352,7 +351,7 @@ pdd_status pdd_pack_mask(const uint8_t *mask, int32_t n_rows, int32_t batch, int
 /*
  * Bytes of DEVICE scratch `which_call` can use for this descriptor (0 when it
  * has no use for any).  At most 8 * n_kv_heads * total_k * 4 bytes, for the
- * chunked call with head_dim 128 at most ceil(max_seqlen_q / 128) * n_q_heads *
+ * chunked call at most ceil(max_seqlen_q / 128) * n_q_heads *
  * total_k * 4 bytes and 256 MiB; never grows with Nq*Nk: the attention weights
  * are not materialised (Section 3.2 "Preliminaries").  The figure depends on
  * the descriptor, on PDD_OPT_ATTN_WAVES and on the number of compute units of
