@@ -177,8 +177,9 @@ def test_importance_with_and_without_scratch(name):
     elif name == "chunk-ragged":   # ragged chunks with 16 query heads per KV head
         wl = W.make_custom("t", [200, 256, 77, 256], [200 + 9000, 256 + 7000, 77 + 8000, 256 + 8100], 32, 2, 128, 0,
                            "1/4", seed=41, chunked=True)
-    elif name == "chunk-tiles":    # chunks of several 256-row query tiles, one of them a single row,
-        wl = W.make_custom("t", [700, 1, 513, 256], [700 + 1500, 1 + 900, 513, 256 + 64], 8, 2, 128, 0,   # one without a prefix
+    elif name == "chunk-tiles":    # chunks of several 256-row query tiles; one without queries (its keys
+        # must come out as zeros), one without a prefix, one of a single row
+        wl = W.make_custom("t", [700, 0, 513, 256, 1], [700 + 1500, 300, 513, 256 + 64, 1 + 900], 8, 2, 128, 0,
                            "1/4", seed=43, chunked=True)
     else:                          # head_dim 64 has no sweep: the row split takes all of the scratch
         wl = W.make_custom("t", [256, 200, 256, 256], [256 + 8000, 200 + 9000, 256 + 8100, 256 + 7000], 32, 2, 64, 0,
