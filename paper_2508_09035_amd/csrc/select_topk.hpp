@@ -265,7 +265,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelP
 // search that leaves the block-wide probes (each one costs a barrier) as soon as the keys still
 // in the bracket fit into one wave's registers; that wave finishes the bisection on its own.
 // ---------------------------------------------------------------------------
-constexpr int kSelWaveKeys = 2048;     // bracket size at which one wave takes over (32 keys per lane)
+constexpr int kSelMaxProbes = 72;       // a 32-bit bracket needs at most 2 x 32 probes (see next_probe)
 
 // inclusive prefix sum over the 64 lanes of a wave (DPP row shifts and row broadcasts)
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
@@ -296,15 +296,57 @@ __device__ __forceinline__ uint32_t next_probe(uint32_t lo, uint32_t hi, uint32_
     return hi - min(down, span - 1u);
 }
 
-template <int QPT>
-__global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const SelParams p)
+// the same over N independent values per lane, one step over all of them at a time: consecutive
+// instructions are independent, so none of them waits for the DPP hazard of its predecessor
+template <int N>
+__device__ __forceinline__ void wave_incl_scan_n(uint32_t (&x)[N])
 {
-    __shared__ uint32_t wred[2][kSelWaves];
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x[i], 0x111, 0xf, 0xf, true);
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x[i], 0x112, 0xf, 0xf, true);
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x[i], 0x114, 0xf, 0xf, true);
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x[i], 0x118, 0xf, 0xf, true);
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x[i], 0x142, 0xa, 0xf, false);
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x[i], 0x143, 0xc, 0xf, false);
+}
+
+// minimum / maximum over the 64 lanes of a wave, valid in lane 63 (same DPP pattern as the scan)
+__device__ __forceinline__ void wave_min_max(uint32_t &mn, uint32_t &mx)
+{
+    // lanes without a source keep their own value (old = the value itself)
+#define PDD_MINMAX_STEP(CTRL, ROWS)                                                                         \
+    {                                                                                                       \
+        const uint32_t a = (uint32_t)__builtin_amdgcn_update_dpp((int)mn, (int)mn, CTRL, ROWS, 0xf, false); \
+        const uint32_t b = (uint32_t)__builtin_amdgcn_update_dpp((int)mx, (int)mx, CTRL, ROWS, 0xf, false); \
+        mn = min(mn, a);                                                                                    \
+        mx = max(mx, b);                                                                                    \
+    }
+    PDD_MINMAX_STEP(0x111, 0xf)
+    PDD_MINMAX_STEP(0x112, 0xf)
+    PDD_MINMAX_STEP(0x114, 0xf)
+    PDD_MINMAX_STEP(0x118, 0xf)
+    PDD_MINMAX_STEP(0x142, 0xa)
+    PDD_MINMAX_STEP(0x143, 0xc)
+#undef PDD_MINMAX_STEP
+}
+
+// At most 64 vector registers, so that two workgroups (8 waves per SIMD) share a compute unit: the
+// kernel lives on overlapping one row's barriers and latencies with another row's work
+// (512 rows of 32768: 2.29 TB/s with two workgroups per compute unit, 1.85 with one).
+template <int QPT>
+__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void select_topk_quad_kernel(const SelParams p)
+{
     __shared__ uint32_t wave_min[kSelWaves], wave_max[kSelWaves];
     __shared__ uint32_t cnt[kSelWaves * QPT];          // per (i, wave): gt count | eq count << 16
-    __shared__ uint32_t cnt_wave_tot[kSelWaves];
-    __shared__ uint32_t fin_keys[kSelWaveKeys];
-    __shared__ uint32_t fin_T, fin_above, head_tot;
+    __shared__ uint32_t probe_tot[kSelMaxProbes];      // count of probe number p, summed over the waves
+    __shared__ __attribute__((aligned(16))) uint32_t fin_keys[kSelFinish + 4];
+    __shared__ uint32_t fin_count, fin_T, fin_above, head_tot;
 
     const int b = blockIdx.x, g = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -351,144 +393,104 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
     const uint32_t khead = has_head ? order_key(seq[c0 + tid]) : 0u;
     const float *qbase = seq + c0 + nhead;                       // 16-byte aligned
     uint32_t key[QPT][4];
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
     for (int i = 0; i < QPT; ++i) {
-        const int x0 = 4 * (i * kSelThreads + tid);              // index inside the quad part
-        float f[4] = {0.f, 0.f, 0.f, 0.f};
-        if (x0 + 3 < nq_el) {
-            const float4 t = *(const float4 *)(qbase + x0);
-            f[0] = t.x;  f[1] = t.y;  f[2] = t.z;  f[3] = t.w;
+        const int xw = 4 * (i * kSelThreads + 64 * wave_u);      // the wave's first index of this step
+        if (xw + 255 < nq_el) {                                  // all of its 64 quads lie inside the row
+            const float4 t = *(const float4 *)(qbase + xw + 4 * lane);
+            key[i][0] = order_key(t.x);  key[i][1] = order_key(t.y);
+            key[i][2] = order_key(t.z);  key[i][3] = order_key(t.w);
         } else {
+            const int x0 = xw + 4 * lane;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (x0 + j < nq_el) f[j] = qbase[x0 + j];
+            for (int j = 0; j < 4; ++j) key[i][j] = (x0 + j < nq_el) ? order_key(qbase[x0 + j]) : 0u;
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) key[i][j] = (x0 + j < nq_el) ? order_key(f[j]) : 0u;
     }
-    uint32_t kmin = has_head ? khead : 0xffffffffu, kmax = khead;
+    // row range over the real keys: an empty slot (key 0) wraps to the largest value under key - 1
+    // and so never is the minimum
+    uint32_t kmin = khead - 1u, kmax = khead;
 #pragma unroll
-    for (int i = 0; i < QPT; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool in = 4 * (i * kSelThreads + tid) + j < nq_el;
-            kmin = in ? min(kmin, key[i][j]) : kmin;
-            kmax = max(kmax, key[i][j]);
-        }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
+    for (int i = 0; i < QPT; ++i) {
+        kmin = min(kmin, min(min(key[i][0] - 1u, key[i][1] - 1u), min(key[i][2] - 1u, key[i][3] - 1u)));
+        kmax = max(kmax, max(max(key[i][0], key[i][1]), max(key[i][2], key[i][3])));
     }
-    if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
+    wave_min_max(kmin, kmax);
+    if (lane == 63) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
+    if (tid < kSelMaxProbes) probe_tot[tid] = 0;
+    if (tid < kSelFinish + 4) fin_keys[tid] = 0;
+    if (tid == 0) fin_count = 0;
     __syncthreads();
+    kmin = wave_min[0];  kmax = wave_max[0];
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
+    for (int w = 1; w < kSelWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
+    kmin += 1u;                                                  // back from key - 1 (kk >= 1: the row has a real key)
 
-    // ---- threshold search, block-wide part: bisection on the key value as in the kernel above,
-    // until at most kSelWaveKeys keys are left in the bracket [lo, hi]; every probed value is
-    // > lo >= kmin > 0, so empty slots never count.
+    // ---- threshold search: largest T in [kmin, kmax] with count(key >= T) >= kk, by probes on the
+    // key value with the bracket [lo, hi] and the two counts c_lo = count(key >= lo) >= kk >
+    // c_above = count(key > hi) (see next_probe).  Every probed value is > lo >= kmin > 0, so empty
+    // slots never count.  The waves' counts of a probe meet in an LDS counter of their own (integer
+    // atomics; one fresh counter per probe, so none is ever cleared), which every thread reads
+    // back after the barrier.  Once at most kSelFinish keys are left inside the bracket they are
+    // collected in LDS (in any order) and one wave ranks them directly.
     uint32_t lo = kmin, hi = kmax;
     uint32_t c_lo = (uint32_t)n, c_above = 0;
-    int par = 0;
     bool interp = true;
-    while (lo < hi && c_lo - c_above > (uint32_t)kSelWaveKeys) {
+    int probe = 0;
+    while (lo < hi && c_lo - c_above > (uint32_t)kSelFinish) {
         const uint32_t inside = c_lo - c_above;
         const uint32_t mid = next_probe(lo, hi, inside, (uint32_t)kk - c_above, interp);
+        // Half of the comparisons are counted with a ballot and a scalar population count, half per
+        // lane on the vector unit with one wave sum at the end.  The 16 waves of the workgroup (and
+        // a second workgroup on the same compute unit) share one scalar unit: all on it, the probe
+        // queues there (1.87 TB/s over 512 rows of 32768); all on the vector unit is slower again
+        // (2.17 TB/s); the split reaches 2.29 TB/s.
         uint32_t c = (uint32_t)__popcll(__ballot(khead >= mid));
+        uint32_t cl[2] = {0u, 0u};
 #pragma unroll
-        for (int i = 0; i < QPT; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) c += (uint32_t)__popcll(__ballot(key[i][j] >= mid));
-        if (lane == 0) wred[par][wave] = c;
+        for (int i = 0; i < QPT; ++i) {
+            c += (uint32_t)__popcll(__ballot(key[i][0] >= mid));
+            c += (uint32_t)__popcll(__ballot(key[i][1] >= mid));
+            cl[0] += key[i][2] >= mid ? 1u : 0u;
+            cl[1] += key[i][3] >= mid ? 1u : 0u;
+        }
+        c += (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan(cl[0] + cl[1]), 63);
+        if (lane == 0) atomicAdd(&probe_tot[probe], c);
         __syncthreads();
-        uint32_t tot = 0;
-#pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) tot += wred[par][w];
-        par ^= 1;
+        const uint32_t tot = probe_tot[probe];
+        ++probe;
         if (tot >= (uint32_t)kk) { lo = mid; c_lo = tot; }
         else { hi = mid - 1u; c_above = tot; }
         interp = !interp || 4u * (c_lo - c_above) <= inside;
     }
     if (lo < hi) {
-        // ---- the keys still inside [lo, hi] (at most kSelWaveKeys) go to LDS, in any order ...
-        // (lo >= kmin > 0: empty slots are outside the bracket)
-        uint32_t mine = (khead >= lo && khead <= hi) ? 1u : 0u;
-#pragma unroll
-        for (int i = 0; i < QPT; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) mine += (key[i][j] >= lo && key[i][j] <= hi) ? 1u : 0u;
-        const uint32_t incl = wave_incl_scan(mine);
-        if (lane == 63) cnt_wave_tot[wave] = incl;
-        __syncthreads();
-        uint32_t pos = incl - mine, m_tot = 0;
-#pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) {               // independent reads, no trip count to wait for
-            const uint32_t t = cnt_wave_tot[w];
-            pos += w < wave ? t : 0u;
-            m_tot += t;
-        }
-        if (khead >= lo && khead <= hi) fin_keys[pos++] = khead;
+        // at most kSelFinish keys lie in [lo, hi] (empty slots, key 0 < lo, fall outside by the
+        // unsigned wrap): the (kk - c_above)-th largest of them is T
+        const uint32_t width = hi - lo;
+        if (khead - lo <= width) fin_keys[atomicAdd(&fin_count, 1u)] = khead;
 #pragma unroll
         for (int i = 0; i < QPT; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (key[i][j] >= lo && key[i][j] <= hi) fin_keys[pos++] = key[i][j];
+                if (key[i][j] - lo <= width) fin_keys[atomicAdd(&fin_count, 1u)] = key[i][j];
         __syncthreads();
-        // ---- ... and one wave, KPL of them per lane, continues the bisection without barriers
-        // until at most kSelFinish keys are left, which it ranks directly: the r-th largest of
-        // the m_tot keys, r = kk - c_above
         if (wave == 0) {
-            constexpr int KPL = kSelWaveKeys / 64;
-            uint32_t fk[KPL];
+            const int m = (int)fin_count;                                 // <= kSelFinish = 64
+            const uint32_t mine_k = lane < m ? fin_keys[lane] : 0u;
+            uint32_t gt = 0, ge = 0;
+            for (int j0 = 0; j0 < m; j0 += 4) {                           // slots past m hold 0: below every key
+                const uint4 o4 = *(const uint4 *)(fin_keys + j0);
+                const uint32_t o[4] = {o4.x, o4.y, o4.z, o4.w};
 #pragma unroll
-            for (int t = 0; t < KPL; ++t) fk[t] = (t * 64 + lane) < (int)m_tot ? fin_keys[t * 64 + lane] : 0u;
-            const uint32_t r = (uint32_t)kk - c_above;              // 1 <= r <= m_tot
-            uint32_t wlo = lo, whi = hi;
-            uint32_t w_ge = m_tot, above = 0;                       // count(key >= wlo), count(key > whi)
-            bool winterp = true;
-            while (wlo < whi && w_ge - above > (uint32_t)kSelFinish) {
-                const uint32_t inside = w_ge - above;
-                const uint32_t mid = next_probe(wlo, whi, inside, r - above, winterp);
-                // per-lane counts on four independent chains, one wave sum at the end (a ballot and
-                // a scalar population count per key would wait for each other with one wave running)
-                uint32_t cl[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-                for (int t = 0; t < KPL; ++t) cl[t & 3] += fk[t] >= mid ? 1u : 0u;
-                const uint32_t c = (uint32_t)__builtin_amdgcn_readlane(
-                    (int)wave_incl_scan((cl[0] + cl[1]) + (cl[2] + cl[3])), 63);
-                if (c >= r) { wlo = mid; w_ge = c; }
-                else { whi = mid - 1u; above = c; }
-                winterp = !winterp || 4u * (w_ge - above) <= inside;
-            }
-            uint32_t T_w = wlo;
-            if (wlo < whi) {
-                // the keys inside [wlo, whi] (at most kSelFinish) in the first LDS slots, then the
-                // (r - above)-th largest of them by counting
-                const uint64_t lt_mask = (1ull << lane) - 1ull;
-                uint32_t m = 0;
-#pragma unroll
-                for (int t = 0; t < KPL; ++t) {
-                    const bool inb = fk[t] >= wlo && fk[t] <= whi;      // empty slots hold 0 < wlo
-                    const uint64_t bal = __ballot(inb);
-                    if (inb) fin_keys[m + __popcll(bal & lt_mask)] = fk[t];
-                    m += (uint32_t)__popcll(bal);
+                for (int x = 0; x < 4; ++x) {
+                    gt += o[x] > mine_k ? 1u : 0u;
+                    ge += o[x] >= mine_k ? 1u : 0u;
                 }
-                const uint32_t mine_k = lane < (int)m ? fin_keys[lane] : 0u;
-                uint32_t gt = 0, ge = 0;
-                for (uint32_t j = 0; j < m; ++j) {
-                    const uint32_t o = fin_keys[j];
-                    gt += o > mine_k ? 1u : 0u;
-                    ge += o >= mine_k ? 1u : 0u;
-                }
-                const uint32_t rr = r - above;                             // 1 <= rr <= m
-                const bool hit = lane < (int)m && gt < rr && rr <= ge;     // every hit lane holds the same key
-                const uint64_t hb = __ballot(hit);
-                const int src = hb ? (int)__builtin_ctzll(hb) : 0;
-                T_w = (uint32_t)__shfl((int)mine_k, src, 64);
-                above += (uint32_t)__shfl((int)gt, src, 64);
             }
-            if (lane == 0) { fin_T = T_w; fin_above = c_above + above; }
+            const uint32_t r = (uint32_t)kk - c_above;                    // 1 <= r <= m
+            const bool hit = lane < m && gt < r && r <= ge;               // every hit lane holds the same key
+            const uint64_t hb = __ballot(hit);
+            if (hb != 0 && lane == (int)__builtin_ctzll(hb)) { fin_T = mine_k; fin_above = c_above + gt; }
         }
         __syncthreads();
         lo = fin_T;
@@ -505,7 +507,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
         pre_head = incl - c_head;
         if (lane == 63) head_tot = incl;
     }
-    uint32_t pre[QPT];                      // exclusive prefix inside the wave, packed gt | eq << 16
+    uint32_t pre[QPT];                      // prefix inside the wave, packed gt | eq << 16
 #pragma unroll
     for (int i = 0; i < QPT; ++i) {
         uint32_t c = 0;
@@ -514,21 +516,38 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
             c += key[i][j] > T ? 1u : 0u;
             c += key[i][j] == T ? 0x10000u : 0u;
         }
-        const uint32_t incl = wave_incl_scan(c);
-        pre[i] = incl - c;
-        if (lane == 63) cnt[i * kSelWaves + wave] = incl;
+        pre[i] = c;
+    }
+    {
+        uint32_t incl[QPT];
+#pragma unroll
+        for (int i = 0; i < QPT; ++i) incl[i] = pre[i];
+        wave_incl_scan_n(incl);
+#pragma unroll
+        for (int i = 0; i < QPT; ++i) {
+            pre[i] = incl[i] - pre[i];                 // exclusive
+            if (lane == 63) cnt[i * kSelWaves + wave] = incl[i];
+        }
     }
     __syncthreads();
-    constexpr int NC = kSelWaves * QPT;                 // <= 128 entries
+    // every wave scans the (step, wave) totals itself (at most 128 of them, two per lane) and picks
+    // the offsets of its own QPT steps: no further barrier
+    constexpr int NC = kSelWaves * QPT;
+    uint32_t step_off[QPT];                 // keys > T | == T << 16 before this wave's part of step i
+    uint32_t eq_total;
     {
-        const uint32_t v = tid < NC ? cnt[tid] : 0u;
-        const uint32_t incl = wave_incl_scan(v);
-        if (lane == 63) cnt_wave_tot[wave] = incl;
-        __syncthreads();
-        uint32_t wave_off = head_tot;
-        for (int w = 0; w < wave; ++w) wave_off += cnt_wave_tot[w];
-        if (tid < NC) cnt[tid] = wave_off + incl - v;   // exclusive prefix over the head and (i, wave)
-        __syncthreads();
+        uint32_t v[2] = {lane < NC ? cnt[lane] : 0u, 64 + lane < NC ? cnt[64 + lane] : 0u};
+        uint32_t sc[2] = {v[0], v[1]};
+        wave_incl_scan_n(sc);
+        const uint32_t tot0 = (uint32_t)__builtin_amdgcn_readlane((int)sc[0], 63);
+        const uint32_t ex0 = sc[0] - v[0] + head_tot, ex1 = sc[1] - v[1] + tot0 + head_tot;
+#pragma unroll
+        for (int i = 0; i < QPT; ++i) {
+            const int e = i * kSelWaves + wave_u;
+            step_off[i] = e < 64 ? (uint32_t)__builtin_amdgcn_readlane((int)ex0, e)
+                                 : (uint32_t)__builtin_amdgcn_readlane((int)ex1, e - 64);
+        }
+        eq_total = (head_tot + tot0 + (uint32_t)__builtin_amdgcn_readlane((int)sc[1], 63)) >> 16;
     }
 
     // ---- stable compaction
@@ -538,20 +557,39 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_quad_kernel(const Sel
         if (sel) out[gt_before + min(eq_before, krem)] = c0 + tid;
         if (mrow) mrow[c0 + tid] = sel ? 1 : 0;
     }
+    // Common case: every key equal to T is kept (no tie is cut, e.g. T is unique).  A key is then
+    // selected iff it is >= T and its slot is the count of such keys before it.
+    const bool ties_all_kept = (int)eq_total <= krem;
+    // The comparisons of the counting pass are made again here, against a copy of T the compiler
+    // cannot relate to the first: kept alive across the scans, their 64 lane masks per wave do not
+    // fit the scalar registers and are spilled lane by lane.
+    uint32_t Tc = T;
+    asm volatile("" : "+v"(Tc));
 #pragma unroll
     for (int i = 0; i < QPT; ++i) {
         const int x0 = 4 * (i * kSelThreads + tid);
-        const uint32_t before = cnt[i * kSelWaves + wave] + pre[i];
-        int gt_before = (int)(before & 0xffffu), eq_before = (int)(before >> 16);
+        const uint32_t before = step_off[i] + pre[i];
         uint32_t mbytes = 0;
+        if (ties_all_kept) {
+            int pos = (int)(before & 0xffffu) + (int)(before >> 16);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool is_gt = key[i][j] > T, is_eq = key[i][j] == T;    // never true for an empty slot
-            const bool sel = is_gt || (is_eq && eq_before < krem);
-            if (sel) out[gt_before + min(eq_before, krem)] = c0 + nhead + x0 + j;
-            gt_before += is_gt ? 1 : 0;
-            eq_before += is_eq ? 1 : 0;
-            mbytes |= sel ? (1u << (8 * j)) : 0u;
+            for (int j = 0; j < 4; ++j) {
+                const bool sel = key[i][j] >= Tc;                             // never true for an empty slot
+                if (sel) out[pos] = c0 + nhead + x0 + j;
+                pos += sel ? 1 : 0;
+                mbytes |= sel ? (1u << (8 * j)) : 0u;
+            }
+        } else {
+            int gt_before = (int)(before & 0xffffu), eq_before = (int)(before >> 16);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool is_gt = key[i][j] > Tc, is_eq = key[i][j] == Tc;
+                const bool sel = is_gt || (is_eq && eq_before < krem);
+                if (sel) out[gt_before + min(eq_before, krem)] = c0 + nhead + x0 + j;
+                gt_before += is_gt ? 1 : 0;
+                eq_before += is_eq ? 1 : 0;
+                mbytes |= sel ? (1u << (8 * j)) : 0u;
+            }
         }
         if (mrow && x0 < nq_el) {
             uint8_t *mp = mrow + c0 + nhead + x0;                          // 4-byte aligned
