@@ -209,13 +209,13 @@ pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, con
     return nw == 8 ? launch_attn_t<64, 8>(p, blocks, st) : launch_attn_t<64, 4>(p, blocks, st);
 }
 
-template <int EPT>
+template <int QPT>
 void launch_select_reg(const pdd::SelParams &p, dim3 grid, hipStream_t st)
 {
     if (p.pool_r == 0)
-        hipLaunchKernelGGL((pdd::select_topk_reg_kernel<EPT, false>), grid, dim3(pdd::kSelThreads), 0, st, p);
+        hipLaunchKernelGGL((pdd::select_topk_reg_kernel<QPT, false>), grid, dim3(pdd::kSelThreads), 0, st, p);
     else
-        hipLaunchKernelGGL((pdd::select_topk_reg_kernel<EPT, true>), grid, dim3(pdd::kSelThreads), 0, st, p);
+        hipLaunchKernelGGL((pdd::select_topk_reg_kernel<QPT, true>), grid, dim3(pdd::kSelThreads), 0, st, p);
 }
 
 int compute_units()
@@ -487,26 +487,15 @@ pdd_status pdd_select_topk_pooled(const float *scores, int32_t n_heads, int32_t 
     p.pooled_out = pooled_out;
     const dim3 grid((unsigned)batch, (unsigned)n_heads);
     hipStream_t st = (hipStream_t)stream;
-    // unpooled scores from 16-byte aligned tensors: four candidates per lane and step
-    const bool quads = p.pool_r == 0 && (reinterpret_cast<uintptr_t>(scores) & 15u) == 0 &&
-                       (reinterpret_cast<uintptr_t>(out_mask) & 3u) == 0;
-    const int span = max_seqlen_k;
-    if (quads && span <= 4 * pdd::kSelThreads)
-        hipLaunchKernelGGL(pdd::select_topk_quad_kernel<1>, grid, dim3(pdd::kSelThreads), 0, st, p);
-    else if (quads && span <= 8 * pdd::kSelThreads)
-        hipLaunchKernelGGL(pdd::select_topk_quad_kernel<2>, grid, dim3(pdd::kSelThreads), 0, st, p);
-    else if (quads && span <= 16 * pdd::kSelThreads)
-        hipLaunchKernelGGL(pdd::select_topk_quad_kernel<4>, grid, dim3(pdd::kSelThreads), 0, st, p);
-    else if (quads && span <= 32 * pdd::kSelThreads)
-        hipLaunchKernelGGL(pdd::select_topk_quad_kernel<8>, grid, dim3(pdd::kSelThreads), 0, st, p);
-    else if (max_seqlen_k <= 4 * pdd::kSelThreads)
-        launch_select_reg<4>(p, grid, st);
+    // rows of up to 32768 candidates stay in registers (4096 per step and 1024 threads)
+    if (max_seqlen_k <= 4 * pdd::kSelThreads)
+        launch_select_reg<1>(p, grid, st);
     else if (max_seqlen_k <= 8 * pdd::kSelThreads)
-        launch_select_reg<8>(p, grid, st);
+        launch_select_reg<2>(p, grid, st);
     else if (max_seqlen_k <= 16 * pdd::kSelThreads)
-        launch_select_reg<16>(p, grid, st);
+        launch_select_reg<4>(p, grid, st);
     else if (max_seqlen_k <= 32 * pdd::kSelThreads)
-        launch_select_reg<32>(p, grid, st);
+        launch_select_reg<8>(p, grid, st);
     else
         hipLaunchKernelGGL(pdd::select_topk_kernel, grid, dim3(pdd::kSelThreads), 0, st, p);
     const hipError_t e = hipGetLastError();

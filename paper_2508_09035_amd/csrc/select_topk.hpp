@@ -64,206 +64,18 @@ __device__ __forceinline__ uint32_t order_key(float x)
 {
     // monotone map fp32 -> uint32 (larger float <=> larger key); -0.0 == +0.0
     const uint32_t u = __float_as_uint(x + 0.0f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);    // negative: all bits flipped; else the sign bit set
 }
 
 
 // ---------------------------------------------------------------------------
-// Register-resident selection for rows of at most 1024 * EPT candidates.
-// Thread `tid` owns candidates x = i * 1024 + tid, i = 0 .. EPT-1.
-// ---------------------------------------------------------------------------
-// POOL = false: the instantiation for unpooled scores carries none of the pooling code.
-template <int EPT, bool POOL>
-__global__ __launch_bounds__(kSelThreads) void select_topk_reg_kernel(const SelParams p)
-{
-    __shared__ uint32_t wred[2][kSelWaves];            // per-wave partial counts (double buffered)
-    __shared__ uint32_t wave_min[kSelWaves], wave_max[kSelWaves];
-    __shared__ uint32_t cnt[kSelWaves * EPT];          // per (i, wave): gt count | eq count << 16
-    __shared__ uint32_t cnt_wave_tot[kSelWaves];
-    __shared__ uint32_t fin_keys[kSelFinish], fin_count, fin_T, fin_above;
-
-    const int b = blockIdx.x, g = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ks = min(max(p.cu_k[b], 0), p.total_k);
-    const int ke = min(max(p.cu_k[b + 1], ks), p.total_k);
-    const int nk = ke - ks;
-    int c0 = p.cand_b ? p.cand_b[b] : 0;
-    int c1 = p.cand_e ? p.cand_e[b] : nk;
-    c0 = min(max(c0, 0), nk);
-    c1 = min(max(c1, c0), nk);
-    const int n = min(c1 - c0, kSelThreads * EPT);
-    const int keep0 = min(max(p.cu_keep[b], 0), p.total_keep);
-    const int keep1 = min(max(p.cu_keep[b + 1], keep0), p.total_keep);
-    const int slots = keep1 - keep0;
-    const int kk = min(min(max(p.k_per[b], 0), n), slots);
-
-    const float *seq = p.scores + (int64_t)g * p.total_k + ks;
-    int32_t *out = p.out_idx + (int64_t)g * p.total_keep + keep0;
-    uint8_t *mrow = p.out_mask ? p.out_mask + (int64_t)g * p.total_k + ks : nullptr;
-
-    if (p.pooled_out) {
-        float *po = p.pooled_out + (int64_t)g * p.total_k + ks;
-        if constexpr (POOL) {
-            for (int x = tid; x < nk; x += kSelThreads) po[x] = pooled_score(seq, nk, x, p.pool_r, p.pool_mode, p.pool_inv);
-        } else {
-            for (int x = tid; x < nk; x += kSelThreads) po[x] = seq[x];
-        }
-    }
-    if (mrow) {
-        for (int x = tid; x < c0; x += kSelThreads) mrow[x] = 0;
-        for (int x = c0 + n + tid; x < nk; x += kSelThreads) mrow[x] = 0;
-    }
-    for (int x = kk + tid; x < slots; x += kSelThreads) out[x] = -1;
-    if (kk == 0) {
-        if (mrow)
-            for (int x = c0 + tid; x < c0 + n; x += kSelThreads) mrow[x] = 0;
-        return;
-    }
-
-    // ---- keys into registers; row range
-    uint32_t key[EPT];
-    uint32_t kmin = 0xffffffffu, kmax = 0u;
-    if constexpr (!POOL) {
-        // plain loads from clamped (always valid: n >= 1 here) addresses, so that all of them are
-        // in flight before the first one is used
-        float raw[EPT];
-#pragma unroll
-        for (int i = 0; i < EPT; ++i) raw[i] = seq[c0 + min(i * kSelThreads + tid, n - 1)];
-#pragma unroll
-        for (int i = 0; i < EPT; ++i) key[i] = (i * kSelThreads + tid < n) ? order_key(raw[i]) : 0u;
-    } else {
-#pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-            const int x = i * kSelThreads + tid;
-            key[i] = x < n ? order_key(pooled_score(seq, nk, c0 + x, p.pool_r, p.pool_mode, p.pool_inv)) : 0u;
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < EPT; ++i) {
-        const bool in = i * kSelThreads + tid < n;
-        kmin = in ? min(kmin, key[i]) : kmin;
-        kmax = in ? max(kmax, key[i]) : kmax;
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
-    }
-    if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
-
-    // ---- threshold search: largest T in [kmin, kmax] with count(key >= T) >= kk.
-    // Bisection on the key value with the bracket [lo, hi] and the two counts
-    // c_lo = count(key >= lo) >= kk > c_above = count(key > hi); once at most kSelFinish keys
-    // are left inside the bracket they are collected in LDS and ranked directly (about 12
-    // probes instead of 27 for a row of 32768; probing the point where a straight line through
-    // the two counts crosses kk was tried and needs more probes: it converges from one side).
-    // Invalid slots hold key 0 and every probed T is > kmin >= 0, so they never count.
-    uint32_t lo = kmin, hi = kmax;
-    uint32_t c_lo = (uint32_t)n;       // count(key >= lo)
-    uint32_t c_above = 0;              // count(key >= hi + 1) = count(key > T) at the end
-    int par = 0;
-    while (lo < hi && c_lo - c_above > (uint32_t)kSelFinish) {
-        const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
-        uint32_t c = 0;
-#pragma unroll
-        for (int i = 0; i < EPT; ++i) c += (uint32_t)__popcll(__ballot(key[i] >= mid));
-        if (lane == 0) wred[par][wave] = c;
-        __syncthreads();
-        uint32_t tot = 0;
-#pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) tot += wred[par][w];
-        par ^= 1;
-        if (tot >= (uint32_t)kk) { lo = mid; c_lo = tot; }
-        else { hi = mid - 1u; c_above = tot; }
-    }
-    if (lo < hi) {
-        // at most kSelFinish keys lie in [lo, hi]: the (kk - c_above)-th largest of them is T
-        if (tid == 0) fin_count = 0;
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-            const bool in = i * kSelThreads + tid < n;
-            if (in && key[i] >= lo && key[i] <= hi) {
-                const uint32_t slot = atomicAdd(&fin_count, 1u);
-                if (slot < (uint32_t)kSelFinish) fin_keys[slot] = key[i];
-            }
-        }
-        __syncthreads();
-        if (wave == 0) {
-            const uint32_t m = min(fin_count, (uint32_t)kSelFinish);
-            const uint32_t mine_k = lane < (int)m ? fin_keys[lane] : 0u;
-            uint32_t gt = 0, ge = 0;
-            for (uint32_t j = 0; j < m; ++j) {
-                const uint32_t o = fin_keys[j];
-                gt += o > mine_k ? 1u : 0u;
-                ge += o >= mine_k ? 1u : 0u;
-            }
-            const uint32_t r = (uint32_t)kk - c_above;                    // 1 <= r <= m
-            const bool hit = lane < (int)m && gt < r && r <= ge;          // every hit lane holds the same key
-            const uint64_t hb = __ballot(hit);
-            if (hb != 0 && lane == (int)__builtin_ctzll(hb)) { fin_T = mine_k; fin_above = c_above + gt; }
-        }
-        __syncthreads();
-        lo = fin_T;
-        c_above = fin_above;
-    }
-    const uint32_t T = lo;
-    const int krem = kk - (int)c_above;     // ties at T to keep (>= 1), lowest index first
-
-    // ---- per (i, wave) counts of keys > T and == T, scanned in index order (i major, wave minor)
-    uint32_t mine = 0;
-#pragma unroll
-    for (int i = 0; i < EPT; ++i) {
-        const bool in = i * kSelThreads + tid < n;
-        const uint32_t cg = (uint32_t)__popcll(__ballot(in && key[i] > T));
-        const uint32_t ce = (uint32_t)__popcll(__ballot(in && key[i] == T));
-        if (lane == i) mine = cg | (ce << 16);
-    }
-    if (lane < EPT) cnt[lane * kSelWaves + wave] = mine;
-    __syncthreads();
-    constexpr int NC = kSelWaves * EPT;                 // <= 512 entries, one per thread
-    uint32_t v = tid < NC ? cnt[tid] : 0u, incl = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = (uint32_t)__shfl_up((int)incl, off, 64);
-        if (lane >= off) incl += o;
-    }
-    if (lane == 63) cnt_wave_tot[wave] = incl;
-    __syncthreads();
-    uint32_t wave_off = 0;
-    for (int w = 0; w < wave; ++w) wave_off += cnt_wave_tot[w];
-    if (tid < NC) cnt[tid] = wave_off + incl - v;       // exclusive prefix (packed gt | eq << 16)
-    __syncthreads();
-
-    // ---- stable compaction
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int i = 0; i < EPT; ++i) {
-        const int x = i * kSelThreads + tid;
-        const bool in = x < n;
-        const uint32_t before = cnt[i * kSelWaves + wave];
-        const int gt_before = (int)(before & 0xffffu), eq_before = (int)(before >> 16);
-        const bool is_gt = in && key[i] > T, is_eq = in && key[i] == T;
-        const uint64_t be = __ballot(is_eq);
-        const int eq_rank = eq_before + __popcll(be & lt_mask);
-        const bool sel = is_gt || (is_eq && eq_rank < krem);
-        const uint64_t bs = __ballot(sel);
-        const int sel_before = gt_before + min(eq_before, krem);
-        if (sel) out[sel_before + __popcll(bs & lt_mask)] = c0 + x;
-        if (mrow && in) mrow[c0 + x] = sel ? 1 : 0;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Register-resident selection, four consecutive candidates per lane and step (unpooled scores
-// from a 16-byte aligned tensor).  Thread `tid` owns the quads q = i * 1024 + tid, i < QPT, of
-// the row's 16-byte aligned part (the up to three candidates before the first 16-byte boundary
-// sit one each in the first lanes of wave 0).  Against the one-candidate-per-lane kernel above: 16-byte loads, the mask written four bytes at a time, and a threshold
-// search that leaves the block-wide probes (each one costs a barrier) as soon as the keys still
-// in the bracket fit into one wave's registers; that wave finishes the bisection on its own.
+// Register-resident selection for rows of at most 4096 * QPT candidates, four consecutive
+// candidates per lane and step.  Thread `tid` owns the quads q = i * 1024 + tid, i < QPT, of the
+// row's part that starts at a 16-byte boundary of the score tensor (the up to three candidates
+// before it sit one each in the first lanes of wave 0): 16-byte loads, the mask written four
+// bytes at a time where the mask tensor's alignment allows it.
+// POOL = true ranks the 1-D pooled scores (evaluated while loading; no 16-byte loads then);
+// the instantiation for unpooled scores carries none of the pooling code.
 // ---------------------------------------------------------------------------
 constexpr int kSelMaxProbes = 72;       // a 32-bit bracket needs at most 2 x 32 probes (see next_probe)
 
@@ -338,9 +150,9 @@ __device__ __forceinline__ void wave_min_max(uint32_t &mn, uint32_t &mx)
 // At most 64 vector registers, so that two workgroups (8 waves per SIMD) share a compute unit: the
 // kernel lives on overlapping one row's barriers and latencies with another row's work
 // (512 rows of 32768: 2.29 TB/s with two workgroups per compute unit, 1.85 with one).
-template <int QPT>
+template <int QPT, bool POOL>
 __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void select_topk_quad_kernel(const SelParams p)
+void select_topk_reg_kernel(const SelParams p)
 {
     __shared__ uint32_t wave_min[kSelWaves], wave_max[kSelWaves];
     __shared__ uint32_t cnt[kSelWaves * QPT];          // per (i, wave): gt count | eq count << 16
@@ -360,21 +172,24 @@ void select_topk_quad_kernel(const SelParams p)
     const int n = min(c1 - c0, 4 * kSelThreads * QPT);
     // Candidates 0 .. nhead-1 (at most three) precede the first 16-byte boundary of the row; lanes
     // 0 .. nhead-1 of wave 0 hold one each.  Candidate nhead + 4q + j is element j of quad q.
-    const int64_t elem0 = (int64_t)g * p.total_k + ks + c0;      // first candidate, in elements of `scores`
-    const int nhead = min((int)((4 - (elem0 & 3)) & 3), n);
+    const float *seq = p.scores + (int64_t)g * p.total_k + ks;
+    const int nhead = POOL ? 0 : min((int)(((16u - ((uint32_t)(uintptr_t)(seq + c0) & 15u)) & 15u) >> 2), n);
     const int nq_el = n - nhead;                                 // candidates inside quads
     const int keep0 = min(max(p.cu_keep[b], 0), p.total_keep);
     const int keep1 = min(max(p.cu_keep[b + 1], keep0), p.total_keep);
     const int slots = keep1 - keep0;
     const int kk = min(min(max(p.k_per[b], 0), n), slots);
 
-    const float *seq = p.scores + (int64_t)g * p.total_k + ks;
     int32_t *out = p.out_idx + (int64_t)g * p.total_keep + keep0;
     uint8_t *mrow = p.out_mask ? p.out_mask + (int64_t)g * p.total_k + ks : nullptr;
 
     if (p.pooled_out) {
         float *po = p.pooled_out + (int64_t)g * p.total_k + ks;
-        for (int x = tid; x < nk; x += kSelThreads) po[x] = seq[x];
+        if constexpr (POOL) {
+            for (int x = tid; x < nk; x += kSelThreads) po[x] = pooled_score(seq, nk, x, p.pool_r, p.pool_mode, p.pool_inv);
+        } else {
+            for (int x = tid; x < nk; x += kSelThreads) po[x] = seq[x];
+        }
     }
     if (mrow) {
         for (int x = tid; x < c0; x += kSelThreads) mrow[x] = 0;
@@ -391,13 +206,19 @@ void select_topk_quad_kernel(const SelParams p)
     // every finite score.
     const bool has_head = tid < nhead;
     const uint32_t khead = has_head ? order_key(seq[c0 + tid]) : 0u;
-    const float *qbase = seq + c0 + nhead;                       // 16-byte aligned
+    const float *qbase = seq + c0 + nhead;                       // 16-byte aligned (unpooled)
     uint32_t key[QPT][4];
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
     for (int i = 0; i < QPT; ++i) {
         const int xw = 4 * (i * kSelThreads + 64 * wave_u);      // the wave's first index of this step
-        if (xw + 255 < nq_el) {                                  // all of its 64 quads lie inside the row
+        if constexpr (POOL) {
+            const int x0 = xw + 4 * lane;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                key[i][j] = (x0 + j < nq_el)
+                    ? order_key(pooled_score(seq, nk, c0 + x0 + j, p.pool_r, p.pool_mode, p.pool_inv)) : 0u;
+        } else if (xw + 255 < nq_el) {                           // all of its 64 quads lie inside the row
             const float4 t = *(const float4 *)(qbase + xw + 4 * lane);
             key[i][0] = order_key(t.x);  key[i][1] = order_key(t.y);
             key[i][2] = order_key(t.z);  key[i][3] = order_key(t.w);
@@ -560,6 +381,8 @@ void select_topk_quad_kernel(const SelParams p)
     // Common case: every key equal to T is kept (no tie is cut, e.g. T is unique).  A key is then
     // selected iff it is >= T and its slot is the count of such keys before it.
     const bool ties_all_kept = (int)eq_total <= krem;
+    // the quads' mask bytes go out as one 4-byte store where the mask tensor is aligned like that
+    const bool mask_dwords = mrow && (((uint32_t)(uintptr_t)(mrow + c0 + nhead)) & 3u) == 0;
     // The comparisons of the counting pass are made again here, against a copy of T the compiler
     // cannot relate to the first: kept alive across the scans, their 64 lane masks per wave do not
     // fit the scalar registers and are spilled lane by lane.
@@ -592,8 +415,8 @@ void select_topk_quad_kernel(const SelParams p)
             }
         }
         if (mrow && x0 < nq_el) {
-            uint8_t *mp = mrow + c0 + nhead + x0;                          // 4-byte aligned
-            if (x0 + 3 < nq_el) *(uint32_t *)mp = mbytes;
+            uint8_t *mp = mrow + c0 + nhead + x0;
+            if (mask_dwords && x0 + 3 < nq_el) *(uint32_t *)mp = mbytes;
             else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)

@@ -306,9 +306,12 @@ def test_select_exact_in_every_register_variant(n):
 
 
 @pytest.mark.parametrize("n", [1000, 6000, 12000, 32768])
-def test_select_unaligned_score_tensor(n):
-    """A score tensor that does not start on a 16-byte boundary takes the one-candidate-per-lane
-    kernel (4, 8, 16, 32 keys per thread at these lengths); same exactness."""
+@pytest.mark.parametrize("score_off,mask_off", [(1, 0), (0, 1), (3, 2)])
+def test_select_unaligned_tensors(n, score_off, mask_off):
+    """Score and mask tensors that do not start on a 16-byte / 4-byte boundary: the kernel takes the
+    candidates before the first 16-byte boundary of a row one by one and writes the mask bytes
+    singly where its quads do not line up with 4-byte words (1, 2, 4, 8 quads per thread at these
+    lengths); same exactness."""
     rng = np.random.default_rng(n + 1)
     lens = [n, 77]
     heads = 2
@@ -319,14 +322,19 @@ def test_select_unaligned_score_tensor(n):
     wl.k_keep = np.array([n // 7, 30], dtype=np.int32)
     dev = DeviceWorkload(wl)
     dev.poison()
-    flat = torch.zeros(heads * sum(lens) + 1, dtype=torch.float32, device="cuda")
-    view = flat[1:].view(heads, sum(lens))
+    flat = torch.zeros(heads * sum(lens) + 4, dtype=torch.float32, device="cuda")
+    view = flat[score_off:score_off + heads * sum(lens)].view(heads, sum(lens))
     view.copy_(torch.from_numpy(s.astype(np.float32)))
-    assert view.data_ptr() % 16 == 4
+    assert view.data_ptr() % 16 == 4 * score_off
+    mflat = torch.full((heads * sum(lens) + 4,), 9, dtype=torch.uint8, device="cuda")
+    dev.mask = mflat[mask_off:mask_off + heads * sum(lens)].view(heads, sum(lens))
+    assert dev.mask.data_ptr() % 4 == mask_off
     dev.select(scores=view)
     torch.cuda.synchronize()
     idx, mask = dev.idx.cpu().numpy(), dev.mask.cpu().numpy()
     check_selection(s.astype(np.float32).astype(np.float64), idx, mask, wl, -1, "unaligned fp32")
+    guard = mflat.cpu().numpy()                     # nothing written outside the mask view
+    assert (guard[:mask_off] == 9).all() and (guard[mask_off + heads * sum(lens):] == 9).all()
 
 
 # ------------------------------------------------------ benchmark configurations
