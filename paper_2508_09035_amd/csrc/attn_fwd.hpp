@@ -166,6 +166,10 @@ void attn_fwd_kernel(const AttnParams p)
     uint8_t *Ks = smem_attn;                               // [3][kTileBytes], tile t in buffer t % 3
     uint8_t *Vs = smem_attn + kAttnBufs * kTileBytes;   // [3][kTileBytes]
 
+    // Workgroups go to the 8 XCDs round robin, each XCD with an L2 of its own.  KV head fastest:
+    // where the number of KV heads divides 8 or is a multiple of 8, all workgroups that share the
+    // K and V of a KV head run on the same XCD(s) and find its tiles in that L2; then the query
+    // heads of the group, the sequence, and the query tiles from the last (longest) down.
     int bid = blockIdx.x;
     const int g = bid % p.Hkv;  bid /= p.Hkv;
     const int hg = bid % p.G;   bid /= p.G;
