@@ -238,6 +238,12 @@ def test_workspace_bytes_host_only():
         assert n > 0 and n % plane == 0 and n // plane <= 8
     assert lib.pdd_workspace_bytes(ctypes.byref(d), 3) == 0          # the selection uses none
     assert lib.pdd_workspace_bytes(None, 0) == 0
+    # the chunked call asks for the sweep's room: one float per query head, 256-row query tile and key
+    assert lib.pdd_workspace_bytes(ctypes.byref(d), 1) == 64 * 1 * 4 * 8448 * 4
+    # ... unless that would pass 256 MiB: then it is the row split of the separate kernel again
+    d.n_q_heads, d.total_q, d.max_seqlen_q = 128, 4 * 4096, 4096    # 128 heads x 16 query tiles x 33792 keys x 4 B
+    n = lib.pdd_workspace_bytes(ctypes.byref(d), 1)
+    assert 0 < n <= 8 * plane
 
 
 def test_noalloc_rejects_shapes_beyond_its_scratch():
