@@ -30,17 +30,21 @@ OTHERS = ("c1", "c2", "c3", "c5")
 # scaled by the same counter's reading for a 1 GiB device copy; see profiles/).  Valid only for the
 # kernel sources with this digest: once they change the figure is reported as null.
 KERNEL_SOURCES = ("attn_fwd.hpp",)
-TRAFFIC = {"c4": {"bytes": 1.679e9, "sources_sha256": "810add4fef65a1ba5d99ee3b5ee90c0fb7963044224a16dd99492f06f0217e78"}}
+TRAFFIC = {"c4": {"bytes": 1.679e9, "sources_sha256": "88f028d9c42203e8569b327921d52638f6fb84e7aea134dc4dbbf982941afb0d"}}
 
 O_ATOL, REL = 2e-2, 1e-3       # the parity bar: O max-abs, log-sum-exp / importance relative
 
 
 def kernel_digest():
+    """Digest of the attention kernel's code: its sources without // comments and white space, so
+    that the stored traffic figure survives a reworded comment and nothing else."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2508_09035_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2508_09035_amd", "csrc", name), "r", encoding="utf-8") as f:
+            code = re.sub(r"//[^\n]*", "", f.read())
+        h.update(re.sub(r"\s+", "", code).encode())
     return h.hexdigest()
 
 

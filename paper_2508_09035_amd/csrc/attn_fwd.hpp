@@ -549,13 +549,13 @@ void attn_fwd_kernel(const AttnParams p)
     // covers every query of the call): with the final log-sum-exp of its 32 rows in hand, each
     // wave walks the same K tiles again, recomputes S = Q K^T with the operands exchanged (lane =
     // key, registers = the wave's 32 query rows), turns it into the normalised probabilities and
-    // adds them up along the query dimension.  The eight waves' column sums of a 64-key tile meet
+    // adds them up along the query dimension.  The waves' column sums of a 64-key tile meet
     // in LDS; one wave adds them in the fixed order wave 0, 1, ... and writes the tile's 64 sums.
     // No atomics: the result does not depend on timing.
     if constexpr (IMP) {
         // LDS: K tiles now rotate through kSweepBufs buffers (the K and V buffers of the first
         // sweep, contiguous); the log-sum-exp exchange and the column sums lie behind them.  A step
-        // is short (16 MFMAs per wave), so a tile is requested five steps before its first use and
+        // is short (D / 8 MFMAs per wave), so a tile is requested five steps before its first use and
         // the wait at the end of a step leaves the two youngest requests in flight.
         float *lse_sh = (float *)(smem_attn + kSweepBufs * kTileBytes);          // [NWAVES][32]
         float *red = (float *)(smem_attn + kSweepBufs * kTileBytes + 1024);      // [2][64][NWAVES]
