@@ -161,10 +161,12 @@ void importance_kernel(const ImpParams p)
             qaddr[kk] = (uint32_t)n * ROW_BYTES + (uint32_t)cs * 16u;
         }
 
-        // the K fragment loads end here: the compiler then places no load waits inside the loop,
-        // where they would also wait for the asynchronous row-block transfers in flight
-        __builtin_amdgcn_s_waitcnt(0);
+        // The first row blocks are requested while the K fragment loads are still in flight; one
+        // wait then ends both (the blocks were requested together and land together).  With the K
+        // loads done here the compiler places no load waits inside the loop, where they would also
+        // wait for the asynchronous row-block transfers in flight.
         for (int i = 0; i < kImpAhead && i < n_items; ++i) issue_item(i, i);
+        __builtin_amdgcn_s_waitcnt(0);
         for (int item = 0; item < n_items; ++item) {
             const int buf = item & (kImpBufs - 1);
             // this block's loads are done once at most the blocks issued after it are outstanding
