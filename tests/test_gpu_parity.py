@@ -305,6 +305,62 @@ def test_select_exact_in_every_register_variant(n):
     _select_case(s, lens, [n // 4, 1, 5], cand=([7, 0, 1], [n - 5, 1, n // 3 - 1]))
 
 
+def _score_row(rng, kind, n):
+    """Score distributions that stress the threshold search: its probes interpolate on the key value."""
+    if kind == 0:
+        return rng.standard_normal(n)
+    if kind == 1:
+        return np.exp(rng.standard_normal(n) * 3 - 9)                             # heavy tail
+    if kind == 2:
+        return rng.integers(0, 7, n).astype(np.float64) / 4                       # few distinct values
+    if kind == 3:
+        return np.full(n, 0.375)                                                  # constant
+    if kind == 4:
+        return rng.standard_normal(n) * 10.0 ** rng.integers(-30, 30, n)          # 60 decades, both signs
+    if kind == 5:
+        x = np.sort(rng.random(n))
+        return x if rng.random() < .5 else x[::-1].copy()                         # sorted either way
+    if kind == 6:
+        x = rng.random(n) ** 8
+        x[rng.integers(0, n, max(1, n // 50))] = 1e30                             # far outliers
+        return x
+    x = np.zeros(n)
+    x[rng.integers(0, n, max(1, n // 100))] = rng.random(max(1, n // 100))       # mostly zero
+    return x
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_select_random_distributions_exact(seed):
+    """Seeded random rows of eight kinds (see _score_row), random lengths up to every register
+    size, candidate ranges, keep counts (0 and everything included) and tensor offsets: the
+    selection on the fp32 scores is exactly the oracle's."""
+    rng = np.random.default_rng(900 + seed)
+    for it in range(12):
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 3))
+        cap = [700, 4096, 5000, 8192, 12000, 16384, 20000, 32768][int(rng.integers(0, 8))]
+        lens = [int(rng.integers(1, cap + 1)) for _ in range(B)]
+        lens[int(rng.integers(0, B))] = cap
+        s = np.stack([np.concatenate([_score_row(rng, int(rng.integers(0, 8)), n) for n in lens]) for _ in range(H)])
+        s = s.astype(np.float32).astype(np.float64)
+        cb = [int(rng.integers(0, max(1, n // 3))) if rng.random() < .5 else 0 for n in lens]
+        ce = [int(rng.integers(b, n + 1)) if rng.random() < .5 else n for b, n in zip(cb, lens)]
+        ks = [int(rng.integers(0, e - b + 1)) if rng.random() < .8 else (e - b) for b, e in zip(cb, ce)]
+        wl = W.make_custom("t", lens, None, 1, 1, 64, 0, seed=0)
+        wl.n_kv_heads = H
+        wl.k_keep = np.array(ks, dtype=np.int32)
+        wl.cand_begin, wl.cand_end = np.array(cb, dtype=np.int32), np.array(ce, dtype=np.int32)
+        dev = DeviceWorkload(wl)
+        dev.poison()
+        off = int(rng.integers(0, 4))
+        flat = torch.zeros(H * sum(lens) + 4, dtype=torch.float32, device="cuda")
+        view = flat[off:off + H * sum(lens)].view(H, sum(lens))
+        view.copy_(torch.from_numpy(s.astype(np.float32)))
+        dev.select(scores=view)
+        torch.cuda.synchronize()
+        check_selection(s, dev.idx.cpu().numpy(), dev.mask.cpu().numpy(), wl, -1,
+                        f"seed {seed} case {it}: lens={lens} keep={ks} cand={cb}..{ce} offset={off}")
+
+
 @pytest.mark.parametrize("n", [1000, 6000, 12000, 32768])
 @pytest.mark.parametrize("score_off,mask_off", [(1, 0), (0, 1), (3, 2)])
 def test_select_unaligned_tensors(n, score_off, mask_off):
