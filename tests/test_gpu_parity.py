@@ -109,6 +109,26 @@ def test_random_shapes(seed):
                     label=f"random {seed}: q={lens_q} chunked={chunked} heads={hq}/{hkv} d={d}")
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_random_chunks_with_long_prefix(seed):
+    """Seeded random chunked problems with several query tiles and prefixes of up to 3000 keys, so
+    that the importance sweep inside the attention kernel runs its pipelined loop, its masked loop
+    and the handover between them; head_dim 64 and 128, 128 and 256 queries per workgroup."""
+    rng = np.random.default_rng(7000 + seed)
+    B = int(rng.integers(1, 4))
+    lens_q = [int(rng.integers(1, 900)) for _ in range(B)]
+    lens_k = [q + int(rng.integers(0, 3000)) for q in lens_q]
+    hq, hkv = [(4, 1), (8, 2), (16, 2), (8, 8)][int(rng.integers(0, 4))]
+    d = int(rng.choice([64, 128]))
+    wl = W.make_custom("t", lens_q, lens_k, hq, hkv, d, 0, "1/3", seed=500 + seed, chunked=True)
+    for b in range(B):
+        if lens_k[b] == lens_q[b]:
+            wl.cand_end[b] = 0
+            wl.k_keep[b] = 0
+    run_and_compare(wl, waves=int(rng.choice([0, 4, 8])),
+                    label=f"chunk {seed}: q={lens_q} k={lens_k} heads={hq}/{hkv} d={d}")
+
+
 def test_empty_sequence_in_batch_and_no_host_copies():
     wl = W.make_custom("t", [40, 0, 129], None, 2, 1, 64, 16, "1/2", seed=9)
     dev = DeviceWorkload(wl)
