@@ -144,14 +144,26 @@ pdd_status launch_attn_t(const pdd::AttnParams &p, int64_t blocks, hipStream_t s
     return launch_attn_kernel(pdd::attn_fwd_kernel<D, NW>, pdd::AttnSmem<D>::BYTES, NW * 64, p, blocks, st);
 }
 
-// Queries per attention workgroup: 8 waves (256 queries) halve the K/V traffic per flop; they
-// are used when there are enough such workgroups for half of the 256 CUs (measured break-even),
-// else 4 waves.
+int compute_units();
+
+// Queries per attention workgroup.  8 waves (256 queries, one workgroup per compute unit) halve the
+// K/V traffic into LDS per flop and win wherever the compute units stay evenly busy; 4 waves (128
+// queries, two workgroups share a compute unit and cover each other's start, end and diagonal
+// region) win on small grids.  Measured on 256 compute units, T = number of 256-query tiles:
+// chunks behind a prefix at least as long (workgroups of nearly equal length) prefer 8 waves from
+// T = 192 on (1.0 against 0.8 PFLOP/s) and 4 waves at T = 128 (0.87 against 0.76); causal prefill,
+// whose workgroups differ in length by the number of query tiles, needs more than one 8-wave
+// workgroup per compute unit before their dynamic placement evens out: 4 waves up to T = 256
+// (0.76 against 0.70 PFLOP/s at 4096 tokens x 16 heads), 8 waves from T = 288 on.
 int attn_rows_per_workgroup(const pdd_attn_desc *d)
 {
     int nw = g_attn_waves;
-    const int64_t tiles256 = (int64_t)((d->max_seqlen_q + 255) / 256) * d->batch * d->n_q_heads;
-    if (nw == 0) nw = tiles256 >= 128 ? 8 : 4;
+    if (nw == 0) {
+        const int64_t tiles256 = (int64_t)((d->max_seqlen_q + 255) / 256) * d->batch * d->n_q_heads;
+        const bool even_lengths = d->max_seqlen_k - d->max_seqlen_q >= d->max_seqlen_q;
+        const int64_t cus = compute_units();
+        nw = tiles256 > (even_lengths ? cus / 2 : cus) ? 8 : 4;
+    }
     return nw * 32;
 }
 
