@@ -464,6 +464,19 @@ def test_c4_long_prompt_sampled_rows():
     assert swapped == 0
 
 
+def test_prompt_of_131072_tokens_sampled_rows():
+    """The paper's prompts reach hundreds of thousands of tokens: one 131072-token prompt (2 query
+    heads on 1 KV head) through the whole path: 512 query tiles, 2048 K/V tiles for the last of
+    them, tile offsets beyond 2^25 bytes, the radix selection.  O and log-sum-exp on the window
+    rows, the first rows, every 8192nd workgroup boundary +- 1 and 64 seeded random rows;
+    importance and the selection in full."""
+    wl = W.make_custom("t", [131072], None, 2, 1, 128, 128, "1/8", seed=131)
+    rows = _sample_rows(wl, 64, tile=8192, first=64)
+    o_err, swapped = run_and_compare(wl, rows=rows)
+    print(f"131072 tokens: {len(rows)} rows, O err {o_err:.4f}, swapped {swapped}")
+    assert swapped == 0
+
+
 @pytest.mark.skipif(os.environ.get("PDD_FULL_C4") != "1",
                     reason="about 10 minutes of fp64 oracle time; set PDD_FULL_C4=1")
 def test_c4_long_prompt_every_row():
