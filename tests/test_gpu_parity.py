@@ -157,6 +157,42 @@ def test_strided_views_of_a_packed_qkv_buffer():
     compare_all(wl, dev, label="strided")
 
 
+def test_kv_rows_a_mebibyte_apart_close_to_the_4_gib_span_limit():
+    """K and V rows 1 MiB apart (views into 3.4 GiB buffers): byte offsets inside the sequence's
+    span run up to 3.4 * 2^30, close to what 32-bit buffer offsets can address; same bits as
+    the packed layout.  With the rows 1.25 MiB apart the span passes the limit and the call is
+    refused on the host."""
+    n, hq, hkv, d = 3000, 4, 2, 128
+    wl = W.make_custom("t", [n], None, hq, hkv, d, 64, "1/2", seed=23)
+    dev = DeviceWorkload(wl)
+    dev.poison()
+    dev.step()
+    torch.cuda.synchronize()
+    want = [x.clone() for x in (dev.o, dev.lse, dev.imp, dev.idx, dev.mask)]
+    row = 1 << 19                                            # elements between rows = 1 MiB
+    bufs = []
+    for name in ("k", "v"):
+        big = torch.empty((n - 1) * row + hkv * d, dtype=torch.bfloat16, device="cuda")
+        view = torch.as_strided(big, (n, hkv, d), (row, d, 1))
+        view.copy_(getattr(dev, name))
+        setattr(dev, name, view)
+        bufs.append(big)
+    dev.poison()
+    dev.step()
+    torch.cuda.synchronize()
+    for what, a, b in zip(("O", "lse", "importance", "indices", "mask"), want,
+                          (dev.o, dev.lse, dev.imp, dev.idx, dev.mask)):
+        assert torch.equal(a, b), what
+    # (3000 + 512) rows x 1 MiB stays below 4 GiB; with rows 1.25 MiB apart it does not
+    wrow = row + (row >> 2)
+    del bufs
+    wide_buf = torch.empty((n - 1) * wrow + hkv * d, dtype=torch.bfloat16, device="cuda")
+    wide = torch.as_strided(wide_buf, (n, hkv, d), (wrow, d, 1))
+    with pytest.raises(Exception, match="4 GiB"):
+        pdd.prefill_attn(dev.q, wide, dev.v, dev.o, dev.lse, dev.imp, dev.cu_q, dev.cu_k,
+                         dev.max_q, dev.max_k, wl.scale, wl.window)
+
+
 def test_standalone_importance_equals_fused_and_is_deterministic():
     wl = W.make_custom("t", [700, 90], None, 8, 2, 128, 64, "1/2", seed=31)
     dev = DeviceWorkload(wl)
