@@ -157,8 +157,8 @@ def test_strided_views_of_a_packed_qkv_buffer():
     compare_all(wl, dev, label="strided")
 
 
-def test_kv_rows_a_mebibyte_apart_close_to_the_4_gib_span_limit():
-    """K and V rows 1 MiB apart (views into 3.4 GiB buffers): byte offsets inside the sequence's
+def test_rows_a_mebibyte_apart_close_to_the_4_gib_span_limit():
+    """Q, K and V rows 1 MiB apart (views into 3.1 GiB buffers): byte offsets inside the sequence's
     span run up to 3.4 * 2^30, close to what 32-bit buffer offsets can address; same bits as
     the packed layout.  With the rows 1.25 MiB apart the span passes the limit and the call is
     refused on the host."""
@@ -171,9 +171,9 @@ def test_kv_rows_a_mebibyte_apart_close_to_the_4_gib_span_limit():
     want = [x.clone() for x in (dev.o, dev.lse, dev.imp, dev.idx, dev.mask)]
     row = 1 << 19                                            # elements between rows = 1 MiB
     bufs = []
-    for name in ("k", "v"):
-        big = torch.empty((n - 1) * row + hkv * d, dtype=torch.bfloat16, device="cuda")
-        view = torch.as_strided(big, (n, hkv, d), (row, d, 1))
+    for name, heads in (("k", hkv), ("v", hkv), ("q", hq)):       # Q too: the importance kernel addresses it like that
+        big = torch.empty((n - 1) * row + heads * d, dtype=torch.bfloat16, device="cuda")
+        view = torch.as_strided(big, (n, heads, d), (row, d, 1))
         view.copy_(getattr(dev, name))
         setattr(dev, name, view)
         bufs.append(big)
