@@ -193,6 +193,32 @@ def test_rows_a_mebibyte_apart_close_to_the_4_gib_span_limit():
                          dev.max_q, dev.max_k, wl.scale, wl.window)
 
 
+def test_two_streams_at_once_with_separate_scratch():
+    """The whole path of two different problems enqueued on two streams (default priority) at the
+    same time, each with its own outputs and scratch: the bits of the runs one after the other."""
+    wls = [W.make_custom("t", [256, 200], [256 + 3000, 200 + 2500], 16, 2, 128, 0, "1/4", seed=61, chunked=True),
+           W.make_custom("t", [1500, 700], None, 8, 2, 128, 64, "1/3", seed=62)]
+    devs = [DeviceWorkload(wl) for wl in wls]
+    want = []
+    for dev in devs:
+        dev.poison()
+        dev.step()
+        torch.cuda.synchronize()
+        want.append([x.clone() for x in (dev.o, dev.lse, dev.imp, dev.idx, dev.mask)])
+        dev.poison()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for _ in range(3):                                      # interleaved enqueues, several rounds
+        for dev, st in zip(devs, streams):
+            with torch.cuda.stream(st):
+                dev.step()
+    torch.cuda.synchronize()
+    for dev, w in zip(devs, want):
+        for what, a, b in zip(("O", "lse", "importance", "indices", "mask"), w,
+                              (dev.o, dev.lse, dev.imp, dev.idx, dev.mask)):
+            assert torch.equal(a, b), what
+
+
 def test_standalone_importance_equals_fused_and_is_deterministic():
     wl = W.make_custom("t", [700, 90], None, 8, 2, 128, 64, "1/2", seed=31)
     dev = DeviceWorkload(wl)
