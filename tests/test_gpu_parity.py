@@ -250,9 +250,9 @@ def test_standalone_importance_equals_fused_and_is_deterministic():
 @pytest.mark.parametrize("name", ["c5", "chunk-ragged", "chunk-tiles", "chunk-d64"])
 def test_importance_with_and_without_scratch(name):
     """The three forms of the importance step in chunked mode, each against the oracle: as a
-    second sweep inside the attention kernel (head_dim 128, all of the scratch the library asks
-    for), as the separate kernel with its window rows divided over several workgroups (one byte
-    less than that, or head_dim 64), and as the separate kernel in a single pass (no scratch).
+    second sweep inside the attention kernel (all of the scratch the library asks for, both head
+    dimensions), as the separate kernel with its window rows divided over several workgroups or in
+    a single pass (one byte less than that: whatever still fits), and without any scratch.
     Partial sums live in the caller's scratch and are added in a fixed order."""
     if name == "c5":
         wl = W.make_workload(name)
@@ -263,7 +263,7 @@ def test_importance_with_and_without_scratch(name):
         # must come out as zeros), one without a prefix, one of a single row
         wl = W.make_custom("t", [700, 0, 513, 256, 1], [700 + 1500, 300, 513, 256 + 64, 1 + 900], 8, 2, 128, 0,
                            "1/4", seed=43, chunked=True)
-    else:                          # head_dim 64 has no sweep: the row split takes all of the scratch
+    else:                          # head_dim 64
         wl = W.make_custom("t", [256, 200, 256, 256], [256 + 8000, 200 + 9000, 256 + 8100, 256 + 7000], 32, 2, 64, 0,
                            "1/4", seed=47, chunked=True)
     oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, -1 if wl.chunked else wl.window)
