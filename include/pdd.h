@@ -119,7 +119,8 @@ enum {
  * chunked entry point otherwise).
  * Limits (PDD_ERR_UNSUPPORTED beyond them; the kernels address with 32-bit byte
  * offsets): the K and V rows of one sequence,
- * (max_seqlen_k + 512) * stride_tok * 2 bytes, must span less than 4 GiB; with
+ * (max_seqlen_k + 512) * stride_tok * 2 bytes, must span less than 4 GiB, and
+ * so must 32 rows of Q (32 * q_stride_tok * 2 bytes); with
  * an importance output the same holds for one sequence's Q rows and for the
  * whole lse tensor (Hq * total_q * 4 bytes).
  */

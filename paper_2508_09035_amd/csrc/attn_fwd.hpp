@@ -93,7 +93,7 @@ constexpr int kSweepAhead = 5;           //   tile t+5 is requested while tile t
 template <int D>
 struct AttnSmem {
     static constexpr int TILE = kBN * D * 2;                       // one K or V tile in LDS, bytes
-    static constexpr int BYTES = 2 * kAttnBufs * TILE;
+    static constexpr int BYTES = (2 * kAttnBufs + 1) * TILE;     // + the fourth Q slot of an 8-wave workgroup
     static constexpr int SWEEP_BYTES = (kSweepBufs + 1) * TILE;    // + exchange area
 };
 constexpr float kLazyLog2 = 8.0f;        // a row's softmax reference may lag its running max by a factor 2^8
@@ -205,14 +205,6 @@ void attn_fwd_kernel(const AttnParams p)
     const int kend = min(nk, min(m0 + BM, nq) + delta);
     const int n_tiles = kend > 0 ? (kend + kBN - 1) / kBN : 0;
 
-    // ---- Q fragments (B operand)
-    bf16x8 qf[NKK];
-    {
-        const uint16_t *qp = p.q + (int64_t)(qs + qrow_c) * p.q_st + (int64_t)h * p.q_sh + 8 * hh;
-#pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) qf[kk] = *(const bf16x8 *)(qp + 16 * kk);
-    }
-
     // ---- buffer resources over this sequence's K / V rows of KV head g
     const uint16_t *kbase = p.k + (int64_t)ks * p.k_st + (int64_t)g * p.k_sh;
     const uint16_t *vbase = p.v + (int64_t)ks * p.v_st + (int64_t)g * p.v_sh;
@@ -276,6 +268,28 @@ void attn_fwd_kernel(const AttnParams p)
             }
         }
     }
+
+    // ---- Q fragments (B operand).  The wave's 32 rows come in whole rows, RPI per instruction,
+    // through LDS in the layout of half a K tile (read per lane from global memory, a row per
+    // lane, every load instruction touches 32 rows 32 bytes at a time and the loads of a
+    // workgroup take longer than the first K and V tiles).  They land in buffers that the first
+    // K and V requests below leave alone; rows past the sequence's end read as zero.
+    // tile-sized LDS slots 2, 4, 5, 6 (K buffer 2, V buffers 1 and 2, one behind them), two waves each
+    const uint32_t q_lds_off = (uint32_t)((wave < 2 ? 2 : 3 + (wave >> 1)) * kTileBytes + (wave & 1) * 32 * ROWB);
+    bf16x8 qf[NKK];
+    auto issue_q = [&]() {
+        const uint16_t *qbase = p.q + (int64_t)(qs + wave_q0) * p.q_st + (int64_t)h * p.q_sh;
+        const uint32_t q_row_bytes = (uint32_t)p.q_st * 2u;
+        const int q_rows = min(32, nq - wave_q0);
+        const uint32_t q_span = q_rows > 0 ? (uint32_t)(q_rows - 1) * q_row_bytes + (uint32_t)ROWB : 0u;
+        const i32x4 rs = make_rsrc(qbase, q_span);
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int r = RPI * i + lane / CH;
+            const int c = (lane % CH) ^ swz_row<D>(r);
+            dma16_to_lds(rs, ks_lds + q_lds_off + 1024 * i, (uint32_t)r * q_row_bytes + (uint32_t)c * 16u);
+        }
+    };
 
     f32x16 oacc[NDB];
 #pragma unroll
@@ -368,13 +382,22 @@ void attn_fwd_kernel(const AttnParams p)
         }
     };
 
-    if (n_tiles > 0) {
-        issue_k(0, 0);
+    // Requests in the order of their first use.  The first barrier waits for K tile 0 and the Q
+    // rows only (loads return in order: the younger requests may still be open); the first QK
+    // block runs while V tile 0 and K tile 1 arrive, and the second barrier publishes those.
+    if (n_tiles > 0) issue_k(0, 0);
+    issue_q();
+    if (n_tiles > 1) {
         issue_v(0, 0);
-        if (n_tiles > 1) issue_k(1, 1);
+        issue_k(1, 1);
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(2 * NLD) : "memory");
+    } else {
+        if (n_tiles > 0) issue_v(0, 0);
+        __builtin_amdgcn_s_waitcnt(0);
     }
-    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) qf[kk] = *(const bf16x8 *)(smem_attn + q_lds_off + kaddr[kk]);
 
     // Scores are pipelined per 32-key block u = 2*tile + blk: while block u goes
     // through softmax and PV, the MFMAs of block u+1 are already issued.  Tile t
@@ -382,6 +405,8 @@ void attn_fwd_kernel(const AttnParams p)
     const int n_blocks = 2 * n_tiles;
     f32x16 sA = zero16, sB = zero16;
     if (n_tiles > 0) qk_block(0, sA);   // block 0 is visible to every wave
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();                    // V tile 0, K tile 1; the next requests overwrite the Q rows
 
     // ---- hot loop: tiles that no wave of the workgroup has to mask (fully visible to the
     // workgroup's first query: 64 (t+1) - 1 <= m0 + delta) and that have a successor tile: no
@@ -524,8 +549,13 @@ void attn_fwd_kernel(const AttnParams p)
     const float l_run = (l_part[0] + l_part[1]) + (l_part[2] + l_part[3]);
     const float l_tot = l_run + xchg_half(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (qrow < nq) {
-        uint16_t *op = p.o + (int64_t)(qs + qrow) * p.o_st + (int64_t)h * p.o_sh;
+    // O leaves through LDS (the K and V buffers are free now): each wave lays its 32 rows out row
+    // by row in a slice of its own, 16-byte chunk c of row r at position c ^ (r mod CH), and then
+    // stores RPI whole rows per instruction, 16 bytes per lane.  (Stored straight from the
+    // accumulator layout, a row per lane, every store instruction touches 32 rows 16 bytes at a
+    // time, and the compute unit spends the time of two to three key tiles issuing them.)
+    {
+        uint8_t *ost = smem_attn + wave * (32 * ROWB);
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
 #pragma unroll
@@ -534,15 +564,28 @@ void attn_fwd_kernel(const AttnParams p)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) x[r] = oacc[db][4 * bq + r] * inv;
                 const bf16x4 y = __builtin_convertvector(x, bf16x4);
-                *(bf16x4 *)(op + 32 * db + 8 * bq + 4 * hh) = y;
+                *(bf16x4 *)(ost + n * ROWB + (((4 * db + bq) ^ (n & (CH - 1))) * 16) + 8 * hh) = y;
             }
         }
-        if (hh == 0) {
-            const float lse = l_tot > 0.f
-                ? (__builtin_amdgcn_logf(l_tot) - ref) * 0.6931471805599453f
-                : -INFINITY;
-            p.lse[(int64_t)h * p.total_q + qs + qrow] = lse;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the slice is read by other lanes of the wave
+        const int sr = lane / CH, sc = lane % CH;
+        uint16_t *op = p.o + (int64_t)(qs + wave_q0 + sr) * p.o_st + (int64_t)h * p.o_sh + 8 * sc;
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = RPI * i + sr;
+            const u32x4 x = *(const u32x4 *)(ost + row * ROWB + ((sc ^ (row & (CH - 1))) * 16));
+            if (wave_q0 + row < nq) *(u32x4 *)(op + (int64_t)(RPI * i) * p.o_st) = x;
         }
+    }
+    if (qrow < nq && hh == 0) {
+        const float lse = l_tot > 0.f
+            ? (__builtin_amdgcn_logf(l_tot) - ref) * 0.6931471805599453f
+            : -INFINITY;
+        p.lse[(int64_t)h * p.total_q + qs + qrow] = lse;
+    }
+    if constexpr (IMP) {   // the second sweep's first requests overwrite the slices
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __syncthreads();
     }
 
     // ---- importance sweep (paper Section 3.2, token importance of an observation window that

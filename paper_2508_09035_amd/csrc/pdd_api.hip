@@ -215,6 +215,9 @@ pdd_status launch_attn(const pdd_attn_desc *d, const void *q, const void *k, con
         const int64_t span = ((int64_t)d->max_seqlen_k + 512) * 2 *
                              (d->k_stride_tok > d->v_stride_tok ? d->k_stride_tok : d->v_stride_tok);
         if (span >= (1LL << 32)) return fail(PDD_ERR_UNSUPPORTED, "a sequence's K/V span must stay below 4 GiB");
+        // and inside the 32 query rows of a wave
+        if ((int64_t)d->q_stride_tok * 2 * 32 >= (1LL << 32))
+            return fail(PDD_ERR_UNSUPPORTED, "32 rows of Q must span less than 4 GiB");
     }
     if (d->head_dim == 128)
         return nw == 8 ? launch_attn_t<128, 8>(p, blocks, st) : launch_attn_t<128, 4>(p, blocks, st);
