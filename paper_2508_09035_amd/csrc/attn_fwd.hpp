@@ -21,7 +21,10 @@
 // Data movement and instruction schedule
 //   * K and V tiles (64 keys x 2 D bytes) go from HBM/L2 straight into LDS with
 //     buffer_load ... lds (no staging registers, no ds_write); rows past the
-//     end of the sequence read as zero through the buffer bounds check.
+//     end of the sequence read as zero through the buffer bounds check.  The
+//     workgroup's Q rows take the same way once, in the layout of K tiles, and
+//     O leaves through LDS as whole rows: every global access of the kernel
+//     moves whole rows, 16 bytes per lane.
 //   * Both tiles are row-major in LDS with a 16-byte-chunk XOR swizzle,
 //       D = 128 (16 chunks per row):  chunk' = chunk ^ (((row & 3) << 2) | ((row >> 2) & 3))
 //       D = 64  (8 chunks per row):   chunk' = chunk ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3))
@@ -32,7 +35,8 @@
 //     register shuffle.
 //   * The loop is software pipelined: the QK^T MFMAs of block j+1 are issued
 //     together with the softmax VALU work of block j, then the PV MFMAs of
-//     block j follow.
+//     block j follow.  The tiles at the diagonal run through the same pipeline
+//     with the causal mask applied to the blocks computed ahead.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -357,31 +361,6 @@ void attn_fwd_kernel(const AttnParams p)
         thr = up ? kLazyLog2 : thr;
     };
 
-    // a block in the log2 domain -> probabilities relative to the reference, added to the row sums
-    auto exp_block = [&](f32x16 &s) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            s[e] = fast_exp2(s[e]);
-            l_part[e & 3] += s[e];
-        }
-    };
-
-    // O^T += V^T P^T for the 32-key block at byte offset `voff` of the V buffers
-    auto pv_block = [&](uint32_t voff, const f32x16 &s) {
-#pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            f32x8 pf;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pf[e] = s[8 * st + e];
-            const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-                const bf16x8 a = lds_read_tr8(vaddr[db][0] + voff + 16 * ROWB * st, vaddr[db][1] + voff + 16 * ROWB * st);
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
-            }
-        }
-    };
-
     // Requests in the order of their first use.  The first barrier waits for K tile 0 and the Q
     // rows only (loads return in order: the younger requests may still be open); the first QK
     // block runs while V tile 0 and K tile 1 arrive, and the second barrier publishes those.
@@ -428,7 +407,8 @@ void attn_fwd_kernel(const AttnParams p)
     };
     // The wave runs at raised issue priority while it has the exponentials to do and at normal
     // priority during its PV MFMAs (measured: 1 % on the 32k prompt, 3 % on constant inputs).
-    auto hot_half = [&](f32x16 &cur, f32x16 &nxt, uint32_t k_next2, uint32_t v_cur) __attribute__((always_inline)) {
+    auto pipe_half = [&](auto mask_c, f32x16 &cur, f32x16 &nxt, uint32_t k_next2, uint32_t v_cur, const int l_nxt, const bool hidden) __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_c)::value;
         __builtin_amdgcn_s_setprio(1);
         bf16x8 vf[2][NDB];
 #pragma unroll
@@ -463,27 +443,62 @@ void attn_fwd_kernel(const AttnParams p)
         }
         __builtin_amdgcn_s_setprio(0);
         load_kf(k_next2);
+        float t_max;
+        if constexpr (!MASK) {
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            const bf16x8 pbs = pb[st];
+            for (int st = 0; st < 2; ++st) {
+                const bf16x8 pbs = pb[st];
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pbs, oacc[db], 0, 0, 0);
-        }
+                for (int db = 0; db < NDB; ++db)
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pbs, oacc[db], 0, 0, 0);
+            }
 #pragma unroll
-        for (int e = 0; e < 16; ++e) l_part[e & 3] += cur[e];      // row sums: also in this phase
-        // The next block enters the log2 domain here, in the phase whose VALU is otherwise idle,
-        // against the present reference (nothing here depends on the check below, so all of it can
-        // be issued between the PV MFMAs).
-        to_log2(nxt);
-        const float t_max = row_max(nxt);
-        // same for this phase: after every PV MFMA one K fragment read and five of the additions,
-        // multiply-adds and max operations above
+            for (int e = 0; e < 16; ++e) l_part[e & 3] += cur[e];      // row sums: also in this phase
+            // The next block enters the log2 domain here, in the phase whose VALU is otherwise idle,
+            // against the present reference (nothing here depends on the check below, so all of it
+            // can be issued between the PV MFMAs).
+            to_log2(nxt);
+            t_max = row_max(nxt);
+            // same for this phase: after every PV MFMA one K fragment read and five of the
+            // additions, multiply-adds and max operations above
 #pragma unroll
-        for (int i = 0; i < 2 * NDB; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // 1 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              // 1 DS read
-            __builtin_amdgcn_sched_group_barrier(0x002, 40 / (2 * NDB), 0); // VALU
+            for (int i = 0; i < 2 * NDB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              // 1 DS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 40 / (2 * NDB), 0); // VALU
+            }
+        } else {
+            // The same work in two parts, with the mask between them for the waves that have a
+            // hidden key in the block (a branch every lane of the wave takes alike): key
+            // 8 (e / 4) + 4 hh + e % 4 of the block is hidden from the row iff it exceeds l_nxt + 4 hh.
+            constexpr int NA = 2 * NDB - 2;       // PV MFMAs before the branch
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+                oacc[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i / NDB][i % NDB], pb[i / NDB], oacc[i % NDB], 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) l_part[e & 3] += cur[e];
+            to_log2(nxt);
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, (NKK + NA - 1) / NA, 0);  // DS reads
+                __builtin_amdgcn_sched_group_barrier(0x002, (32 + NA - 1) / NA, 0);   // VALU
+            }
+            if (hidden) {
+                asm volatile("" ::: "memory");     // stays a branch
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    nxt[e] = 8 * (e >> 2) + (e & 3) > l_nxt ? -INFINITY : nxt[e];
+            }
+#pragma unroll
+            for (int i = NA; i < 2 * NDB; ++i)
+                oacc[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i / NDB][i % NDB], pb[i / NDB], oacc[i % NDB], 0, 0, 0);
+            t_max = row_max(nxt);
+#pragma unroll
+            for (int i = NA; i < 2 * NDB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);              // VALU
+            }
         }
         if (__any(t_max > thr)) renew(t_max, nxt);
     };
@@ -492,57 +507,57 @@ void attn_fwd_kernel(const AttnParams p)
         constexpr int P1 = (PAR + 1) % 3, P2 = (PAR + 2) % 3;
         issue_v(it + 1, P1);
         if (it + 2 < n_tiles) issue_k(it + 2, P2);
-        hot_half(sA, sB, P1 * kTileBytes, PAR * kTileBytes);
-        hot_half(sB, sA, P1 * kTileBytes + 32 * ROWB, PAR * kTileBytes + 32 * ROWB);
+        pipe_half(std::false_type{}, sA, sB, P1 * kTileBytes, PAR * kTileBytes, 0, false);
+        pipe_half(std::false_type{}, sB, sA, P1 * kTileBytes + 32 * ROWB, PAR * kTileBytes + 32 * ROWB, 0, false);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };
+    // The same pipeline for the tiles at and next to the diagonal: the blocks computed ahead
+    // are masked as they enter the log2 domain, before their row max is taken.  A block past the
+    // row's last visible key, past the wave's last row or past the last tile (whose buffer holds
+    // stale rows) comes out all -inf: it renews nothing and adds zeros.  A wave none of whose rows
+    // sees the tile only takes part in the requests and the barrier.
+    const int lim4 = lim - 4 * hh;
+    auto masked_tile = [&](auto par_c, const int it) {
+        constexpr int PAR = decltype(par_c)::value;
+        constexpr int P1 = (PAR + 1) % 3, P2 = (PAR + 2) % 3;
+        if (it + 1 < n_tiles) issue_v(it + 1, P1);
+        if (it + 2 < n_tiles) issue_k(it + 2, P2);
+        if (kBN * it <= wave_lim_max) {
+            const int l1 = lim4 - (kBN * it + 32);
+            const int w1 = wave_lim_min - (kBN * it + 32);      // the same for the wave's first row
+            pipe_half(std::true_type{}, sA, sB, P1 * kTileBytes, PAR * kTileBytes, l1, w1 < 31);
+            pipe_half(std::true_type{}, sB, sA, P1 * kTileBytes + 32 * ROWB, PAR * kTileBytes + 32 * ROWB, l1 - 32, w1 < 63);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
+    // The first block: masked where it touches the diagonal, then every row takes its first
+    // reference from it (key 0 is visible to every row).
     int it = 0;
-    if (n_hot > 0) {
-        to_log2(sA);                                // the first block sets every row's reference
+    if (n_tiles > 0) {
+        if (31 > wave_lim_min) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                sA[e] = 8 * (e >> 2) + (e & 3) > lim4 ? -INFINITY : sA[e];
+        }
+        to_log2(sA);
         renew(row_max(sA), sA);
         load_kf(32 * ROWB);
-        for (; it + 3 <= n_hot; it += 3) {          // unrolled over the three LDS buffers
-            hot_tile(std::integral_constant<int, 0>{}, it);
-            hot_tile(std::integral_constant<int, 1>{}, it + 1);
-            hot_tile(std::integral_constant<int, 2>{}, it + 2);
-        }
-        if (it < n_hot) { hot_tile(std::integral_constant<int, 0>{}, it); ++it; }
-        if (it < n_hot) { hot_tile(std::integral_constant<int, 1>{}, it); ++it; }
-        // the hot loop leaves sA scaled and shifted; the generic loop wants the raw scores of its
-        // first block (one extra QK block per workgroup)
-        qk_block((uint32_t)(it % 3) * kTileBytes, sA);
     }
-
-    // ---- remaining tiles (the diagonal region): per-wave activity and masking
-    auto slow_half = [&](f32x16 &cur, f32x16 &nxt, const int u, uint32_t k_next, uint32_t v_cur) {
-        const int j0 = 32 * u;
-        const bool cur_active = j0 <= wave_lim_max;
-        const bool nxt_active = u + 1 < n_blocks && j0 + 32 <= wave_lim_max;
-        if (nxt_active) qk_block(k_next, nxt);
-        if (cur_active) {
-            if (j0 + 31 > wave_lim_min) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int j = j0 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    if (j > lim) cur[e] = -INFINITY;
-                }
-            }
-            to_log2(cur);                         // masked entries stay -inf
-            const float t_max = row_max(cur);
-            if (__any(t_max > thr)) renew(t_max, cur);
-            exp_block(cur);
-            pv_block(v_cur, cur);
-        }
-    };
-    for (; it < n_tiles; ++it) {
-        const uint32_t b0 = (uint32_t)(it % 3) * kTileBytes, b1 = (uint32_t)((it + 1) % 3) * kTileBytes;
-        if (it + 1 < n_tiles) issue_v(it + 1, (it + 1) % 3);
-        if (it + 2 < n_tiles) issue_k(it + 2, (it + 2) % 3);
-        slow_half(sA, sB, 2 * it, b0 + 32 * ROWB, b0);
-        slow_half(sB, sA, 2 * it + 1, b1, b0 + 32 * ROWB);
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
+    // Plain tiles: the two blocks a tile computes ahead (its own second and the next tile's
+    // first) are visible in full to every row of the workgroup, i.e. all hot tiles but the last.
+    const int n_plain = max(0, n_hot - 1) / 3 * 3;   // whole rounds of the three LDS buffers
+    for (; it < n_plain; it += 3) {
+        hot_tile(std::integral_constant<int, 0>{}, it);
+        hot_tile(std::integral_constant<int, 1>{}, it + 1);
+        hot_tile(std::integral_constant<int, 2>{}, it + 2);
+    }
+    // ---- the last hot tiles and the diagonal region
+    for (; it < n_tiles; it += 3) {
+        masked_tile(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < n_tiles) masked_tile(std::integral_constant<int, 1>{}, it + 1);
+        if (it + 2 < n_tiles) masked_tile(std::integral_constant<int, 2>{}, it + 2);
     }
 
     // ---- epilogue
@@ -570,12 +585,16 @@ void attn_fwd_kernel(const AttnParams p)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the slice is read by other lanes of the wave
         const int sr = lane / CH, sc = lane % CH;
         uint16_t *op = p.o + (int64_t)(qs + wave_q0 + sr) * p.o_st + (int64_t)h * p.o_sh + 8 * sc;
+        u32x4 x[32 / RPI];
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i) {
             const int row = RPI * i + sr;
-            const u32x4 x = *(const u32x4 *)(ost + row * ROWB + ((sc ^ (row & (CH - 1))) * 16));
-            if (wave_q0 + row < nq) *(u32x4 *)(op + (int64_t)(RPI * i) * p.o_st) = x;
+            x[i] = *(const u32x4 *)(ost + row * ROWB + ((sc ^ (row & (CH - 1))) * 16));
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // all reads before the first store
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i)
+            if (wave_q0 + RPI * i + sr < nq) *(u32x4 *)(op + (int64_t)(RPI * i) * p.o_st) = x[i];
     }
     if (qrow < nq && hh == 0) {
         const float lse = l_tot > 0.f
