@@ -383,14 +383,12 @@ void attn_fwd_kernel(const AttnParams p)
     // lives in LDS buffer t % 3; at every tile boundary the current block is in sA.
     const int n_blocks = 2 * n_tiles;
     f32x16 sA = zero16, sB = zero16;
-    if (n_tiles > 0) qk_block(0, sA);   // block 0 is visible to every wave
+    if (n_tiles > 0) qk_block(0, sA);   // every wave has rows that see block 0
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();                    // V tile 0, K tile 1; the next requests overwrite the Q rows
 
-    // ---- hot loop: tiles that no wave of the workgroup has to mask (fully visible to the
-    // workgroup's first query: 64 (t+1) - 1 <= m0 + delta) and that have a successor tile: no
-    // per-wave branches at all.  The scores the last hot tile computes ahead for the first
-    // block of the next (diagonal) tile are masked by the generic loop before they are used.
+    // ---- hot tiles: those that no wave of the workgroup has to mask (fully visible to the
+    // workgroup's first query: 64 (t+1) - 1 <= m0 + delta) and that have a successor tile.
     const int first_lim = m0 + delta;
     const int n_hot = max(0, min((first_lim + 1) / kBN, n_tiles - 1));   // tiles 0 .. n_hot-1
 

@@ -148,8 +148,8 @@ int compute_units();
 
 // Queries per attention workgroup.  8 waves (256 queries, one workgroup per compute unit) halve the
 // K/V traffic into LDS per flop and win wherever the compute units stay evenly busy; 4 waves (128
-// queries, two workgroups share a compute unit and cover each other's start, end and diagonal
-// region) win on small grids.  Measured on 256 compute units, T = number of 256-query tiles:
+// queries: twice as many workgroups of half the rows, which spread more evenly; at head_dim 64
+// two of them also share a compute unit) win on small grids.  Measured on 256 compute units, T = number of 256-query tiles:
 // chunks behind a prefix at least as long (workgroups of nearly equal length) prefer 8 waves from
 // T = 192 on (1.0 against 0.8 PFLOP/s) and 4 waves at T = 128 (0.87 against 0.76); causal prefill,
 // whose workgroups differ in length by the number of query tiles, needs more than one 8-wave

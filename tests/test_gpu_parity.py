@@ -191,6 +191,15 @@ def test_rows_a_mebibyte_apart_close_to_the_4_gib_span_limit():
     with pytest.raises(Exception, match="4 GiB"):
         pdd.prefill_attn(dev.q, wide, dev.v, dev.o, dev.lse, dev.imp, dev.cu_q, dev.cu_k,
                          dev.max_q, dev.max_k, wl.scale, wl.window)
+    # a wave addresses its 32 rows of Q the same way: rows 128 MiB apart are refused as well
+    del wide, wide_buf
+    wl2 = W.make_custom("t", [2], None, hq, hkv, d, 1, "1/2", seed=24)
+    dev2 = DeviceWorkload(wl2)
+    q_buf = torch.empty((1 << 26) + hq * d, dtype=torch.bfloat16, device="cuda")
+    q_wide = torch.as_strided(q_buf, (2, hq, d), (1 << 26, d, 1))
+    with pytest.raises(Exception, match="32 rows of Q"):
+        pdd.prefill_attn(q_wide, dev2.k, dev2.v, dev2.o, dev2.lse, dev2.imp, dev2.cu_q, dev2.cu_k,
+                         dev2.max_q, dev2.max_k, wl2.scale, wl2.window)
 
 
 def test_two_streams_at_once_with_separate_scratch():
