@@ -365,8 +365,10 @@ size_t pdd_workspace_bytes(const pdd_attn_desc *desc, int which_call);
  * Tuning knobs (process-wide, not thread-safe against concurrent launches).
  *   PDD_OPT_ATTN_WAVES: wavefronts per attention workgroup, 4 (128 queries) or
  *   8 (256 queries); 0 = chosen per problem (default).
+ *   PDD_OPT_IMPORTANCE_KEYS: keys per workgroup of the importance kernel, 128
+ *   or 256; 0 = chosen per problem (default).  Results do not depend on it.
  */
-enum { PDD_OPT_ATTN_WAVES = 0 };
+enum { PDD_OPT_ATTN_WAVES = 0, PDD_OPT_IMPORTANCE_KEYS = 1 };
 pdd_status pdd_set_option(int option, int value);
 
 /* Message for the calling thread's most recent non-OK status ("" if none). */

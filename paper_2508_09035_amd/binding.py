@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_PKG_DIR, "libpdd.so")
 _lib = None
 
 OPT_ATTN_WAVES = 0
+OPT_IMPORTANCE_KEYS = 1
 CALL_PREFILL_ATTN, CALL_PREFILL_ATTN_CHUNKED, CALL_TOKEN_IMPORTANCE, CALL_SELECT_TOPK = 0, 1, 2, 3
 
 

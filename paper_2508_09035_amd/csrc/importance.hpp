@@ -9,12 +9,13 @@
 // is recomputed from one QK^T tile and added into a per-key column sum; the
 // attention matrix is never stored.  Work is split over KEYS: a workgroup of 4
 // waves owns 256 keys, each wave 64 of them (two 32-key groups whose K
-// fragments stay in registers as B operands for the whole kernel).  The window
+// fragments stay in registers as B operands for the whole kernel); with KG = 1
+// it owns 128 keys, one 32-key group per wave, which small launches prefer.  The window
 // rows of the G query heads are streamed through LDS in blocks of 32 rows
 // (buffer_load ... lds, double buffered, swizzled like the attention K tile)
 // together with their log-sum-exp values (four buffers, three blocks in flight:
 // with little arithmetic per block the kernel lives on hiding the load latency),
-// so every Q fragment read from LDS feeds two MFMAs and every Q row is fetched
+// so every Q fragment read from LDS feeds KG MFMAs and every Q row is fetched
 // from L2 once per workgroup.
 // S = Q K^T puts key (l % 32) in lane l and 16 query rows in its accumulator
 // registers, so the sum over queries is in-lane; no atomics, fixed summation
@@ -61,7 +62,7 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int D>
+template <int D, int KG = 2>
 __global__ __launch_bounds__(kImpWaves * 64) __attribute__((amdgpu_waves_per_eu(3, 4)))
 void importance_kernel(const ImpParams p)
 {
@@ -84,7 +85,8 @@ void importance_kernel(const ImpParams p)
     const int qs = min(p.cu_q[b], p.total_q), qe = min(p.cu_q[b + 1], p.total_q);
     const int ks = min(p.cu_k[b], p.total_k), ke = min(p.cu_k[b + 1], p.total_k);
     const int nq = qe - qs, nk = ke - ks;
-    const int j_wg0 = kt * kImpBK;
+    constexpr int WKEYS = 32 * KG;               // keys per wave
+    const int j_wg0 = kt * (WKEYS * kImpWaves);
     if (j_wg0 >= nk) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -92,13 +94,13 @@ void importance_kernel(const ImpParams p)
     const int delta = nk - nq;
     const int W = (p.window < 0 || p.window > nq) ? nq : p.window;
     const int iw0 = nq - W;                       // first window row
-    const int jw0 = j_wg0 + 64 * wave;            // first key of this wave
+    const int jw0 = j_wg0 + WKEYS * wave;         // first key of this wave
 
-    // K fragments (B operand) of the wave's two 32-key groups: key j, dims 16 kk + 8 hh .. +7
-    bf16x8 kf[2][NKK];
-    int jkey[2];
+    // K fragments (B operand) of the wave's KG 32-key groups: key j, dims 16 kk + 8 hh .. +7
+    bf16x8 kf[KG][NKK];
+    int jkey[KG];
 #pragma unroll
-    for (int kg = 0; kg < 2; ++kg) {
+    for (int kg = 0; kg < KG; ++kg) {
         jkey[kg] = jw0 + 32 * kg + n;
         const uint16_t *kp = p.k + (int64_t)(ks + min(jkey[kg], nk - 1)) * p.k_st + (int64_t)g * p.k_sh + 8 * hh;
 #pragma unroll
@@ -106,7 +108,7 @@ void importance_kernel(const ImpParams p)
     }
     const float c2 = p.scale_log2;
     constexpr float kLog2e = 1.4426950408889634f;
-    float colsum[2] = {0.f, 0.f};
+    float colsum[KG] = {};
 
     if (nq > 0 && delta >= 0 && W > 0) {
         // row blocks: (head in group, 32-row block of the window); blocks whose rows all lie
@@ -181,41 +183,43 @@ void importance_kernel(const ImpParams p)
             const int i_last = min(i0 + 31, nq - 1);
             if (jw0 <= i_last + delta && jw0 < nk) {       // some row of the block sees some key of the wave
                 const uint8_t *qb = &qs_lds[buf][0];
-                f32x16 s0, s1;
+                f32x16 sc[KG];
                 const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < NKK; ++kk) {
                     const bf16x8 a = *(const bf16x8 *)(qb + qaddr[kk]);
-                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[0][kk], kk == 0 ? zero16 : s0, 0, 0, 0);
-                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[1][kk], kk == 0 ? zero16 : s1, 0, 0, 0);
+#pragma unroll
+                    for (int kg = 0; kg < KG; ++kg)
+                        sc[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[kg][kk], kk == 0 ? zero16 : sc[kg], 0, 0, 0);
                 }
                 // log2-domain LSE of rows 8 (e/4) + 4 hh + (e%4)
                 f32x4 l2[4];
 #pragma unroll
                 for (int bq = 0; bq < 4; ++bq) l2[bq] = *(const f32x4 *)&lse_lds[buf][wave][8 * bq + 4 * hh] * kLog2e;
                 // rows beyond the sequence end or keys beyond a row's reach contribute nothing
-                const bool partial = (i0 + 31 > nq - 1) || (jw0 + 63 > i0 + delta) || (jw0 + 63 > nk - 1);
+                const bool partial = (i0 + 31 > nq - 1) || (jw0 + WKEYS - 1 > i0 + delta) || (jw0 + WKEYS - 1 > nk - 1);
                 if (!partial) {
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        colsum[0] += fast_exp2(fmaf(s0[e], c2, -l2[e >> 2][e & 3]));
-                        colsum[1] += fast_exp2(fmaf(s1[e], c2, -l2[e >> 2][e & 3]));
-                    }
+                    for (int e = 0; e < 16; ++e)
+#pragma unroll
+                        for (int kg = 0; kg < KG; ++kg)
+                            colsum[kg] += fast_exp2(fmaf(sc[kg][e], c2, -l2[e >> 2][e & 3]));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int i = i0 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                        const float p0 = fast_exp2(fmaf(s0[e], c2, -l2[e >> 2][e & 3]));
-                        const float p1 = fast_exp2(fmaf(s1[e], c2, -l2[e >> 2][e & 3]));
-                        colsum[0] += (i < nq && jkey[0] <= i + delta && jkey[0] < nk) ? p0 : 0.f;
-                        colsum[1] += (i < nq && jkey[1] <= i + delta && jkey[1] < nk) ? p1 : 0.f;
+#pragma unroll
+                        for (int kg = 0; kg < KG; ++kg) {
+                            const float pe = fast_exp2(fmaf(sc[kg][e], c2, -l2[e >> 2][e & 3]));
+                            colsum[kg] += (i < nq && jkey[kg] <= i + delta && jkey[kg] < nk) ? pe : 0.f;
+                        }
                     }
                 }
             }
         }
     }
 #pragma unroll
-    for (int kg = 0; kg < 2; ++kg) {
+    for (int kg = 0; kg < KG; ++kg) {
         const float tot = colsum[kg] + xchg_half(colsum[kg]);
         float *dst = p.n_split > 1 ? p.part + (int64_t)split * p.Hkv * p.total_k : p.imp;
         if (hh == 0 && jkey[kg] < nk) dst[(int64_t)g * p.total_k + ks + jkey[kg]] = tot;

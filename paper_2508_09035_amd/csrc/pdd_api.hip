@@ -28,6 +28,7 @@ namespace {
 
 thread_local char g_err[512] = "";
 std::atomic<int> g_attn_waves{0};  // 0 = choose per problem
+std::atomic<int> g_imp_keys{0};    // keys per importance workgroup, 0 = choose per problem
 
 pdd_status fail(pdd_status st, const char *fmt, ...)
 {
@@ -304,12 +305,27 @@ pdd_status launch_importance(const pdd_attn_desc *d, const void *q, const void *
         return fail(PDD_ERR_WORKSPACE, "workspace must be 16-byte aligned");
     p.n_split = split ? importance_split(d, window) : 1;
     p.part = split ? (float *)workspace : nullptr;
-    const int64_t blocks = (int64_t)p.n_ktiles * d->batch * d->n_kv_heads * p.n_split;
+    int64_t blocks = (int64_t)p.n_ktiles * d->batch * d->n_kv_heads * p.n_split;
+    // Up to four workgroups per compute unit the launch runs with half the keys per workgroup
+    // (one 32-key group per wave instead of two): the same blocks of rows per workgroup at half
+    // the work per block, and a workgroup's time is mostly its chain of blocks.  Measured against
+    // 256 keys: 17 -> 12 us on 4096 tokens x 32 heads (128 workgroups become 256), 42 -> 37 us on
+    // the batch of 8 mixed prompts (768 -> 1536), equal on the 32k-token prompt (1024 -> 2048);
+    // beyond that the wide form re-reads the window rows half as often.  Same bits either way.
+    const bool narrow = g_imp_keys ? g_imp_keys == pdd::kImpBK / 2 : blocks <= 4 * (int64_t)compute_units();
+    if (narrow) {
+        p.n_ktiles = (d->max_seqlen_k + pdd::kImpBK / 2 - 1) / (pdd::kImpBK / 2);
+        blocks = (int64_t)p.n_ktiles * d->batch * d->n_kv_heads * p.n_split;
+    }
     if (blocks > 0x7fffffffLL) return fail(PDD_ERR_INVALID_ARG, "launch grid too large");
-    if (d->head_dim == 128)
-        hipLaunchKernelGGL(pdd::importance_kernel<128>, dim3((unsigned)blocks), dim3(pdd::kImpWaves * 64), 0, st, p);
-    else
-        hipLaunchKernelGGL(pdd::importance_kernel<64>, dim3((unsigned)blocks), dim3(pdd::kImpWaves * 64), 0, st, p);
+    const dim3 grid((unsigned)blocks), block(pdd::kImpWaves * 64);
+    if (d->head_dim == 128) {
+        if (narrow) hipLaunchKernelGGL((pdd::importance_kernel<128, 1>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((pdd::importance_kernel<128, 2>), grid, block, 0, st, p);
+    } else {
+        if (narrow) hipLaunchKernelGGL((pdd::importance_kernel<64, 1>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((pdd::importance_kernel<64, 2>), grid, block, 0, st, p);
+    }
     if (split) launch_importance_reduce(p.part, imp, (int64_t)d->n_kv_heads * d->total_k, p.n_split, st);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(PDD_ERR_HIP, "importance launch: %s", hipGetErrorString(e));
@@ -367,6 +383,12 @@ pdd_status pdd_set_option(int option, int value)
     if (option == PDD_OPT_ATTN_WAVES) {
         if (value != 0 && value != 4 && value != 8) return fail(PDD_ERR_INVALID_ARG, "attn waves must be 0, 4 or 8");
         g_attn_waves = value;
+        return PDD_OK;
+    }
+    if (option == PDD_OPT_IMPORTANCE_KEYS) {
+        if (value != 0 && value != pdd::kImpBK / 2 && value != pdd::kImpBK)
+            return fail(PDD_ERR_INVALID_ARG, "importance keys per workgroup must be 0, 128 or 256");
+        g_imp_keys = value;
         return PDD_OK;
     }
     return fail(PDD_ERR_INVALID_ARG, "unknown option %d", option);

@@ -117,6 +117,12 @@ def test_importance_and_select_validation():
     with pytest.raises(pdd.PddError):
         pdd.set_option(pdd.OPT_ATTN_WAVES, 5)
     pdd.set_option(pdd.OPT_ATTN_WAVES, 0)
+    assert pdd.set_option(pdd.OPT_IMPORTANCE_KEYS, 128) is None
+    with pytest.raises(pdd.PddError):
+        pdd.set_option(pdd.OPT_IMPORTANCE_KEYS, 64)
+    pdd.set_option(pdd.OPT_IMPORTANCE_KEYS, 0)
+    with pytest.raises(pdd.PddError):
+        pdd.set_option(7, 0)
     assert pdd.workspace_bytes(good_desc(), 0) < 64 * 64 * 4     # never O(N^2)
 
 

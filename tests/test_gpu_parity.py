@@ -297,6 +297,32 @@ def test_importance_with_and_without_scratch(name):
         pdd.set_option(pdd.OPT_ATTN_WAVES, 0)
 
 
+def test_importance_key_widths_give_the_same_bits():
+    """The importance kernel with 256 and with 128 keys per workgroup (the library picks by launch
+    size): the same column sums bit for bit, on ragged prefill (windows that end inside a key
+    slice, sequences shorter than a slice) and on chunks behind a prefix without scratch; the
+    first against the oracle as well."""
+    cases = [W.make_custom("t", [700, 33, 1290, 128, 5], None, 8, 2, 128, 96, "1/2", seed=71),
+             W.make_custom("t", [300, 64], None, 6, 3, 64, 40, "1/2", seed=72),
+             W.make_custom("t", [256, 77], [256 + 1500, 77 + 900], 8, 2, 128, 0, "1/4", seed=73, chunked=True)]
+    try:
+        for n, wl in enumerate(cases):
+            dev = DeviceWorkload(wl)
+            got = {}
+            for keys in (256, 128):
+                pdd.set_option(pdd.OPT_IMPORTANCE_KEYS, keys)
+                dev.poison()
+                dev.attn(True, use_workspace=False)
+                torch.cuda.synchronize()
+                got[keys] = dev.imp.clone()
+            assert torch.equal(got[256], got[128]), f"case {n}"
+            if n == 0:
+                oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, wl.window)
+                rel_close(got[128].cpu().numpy().astype(np.float64), oI, "128 keys per workgroup")
+    finally:
+        pdd.set_option(pdd.OPT_IMPORTANCE_KEYS, 0)
+
+
 @pytest.mark.parametrize("name", ["c5", "c3", "c4"])
 def test_results_are_bit_identical_run_to_run(name):
     """The whole path twice on the same inputs: identical bits.  Large launches matter here:
