@@ -312,7 +312,9 @@ pdd_status launch_importance(const pdd_attn_desc *d, const void *q, const void *
     // 256 keys: 17 -> 12 us on 4096 tokens x 32 heads (128 workgroups become 256), 42 -> 37 us on
     // the batch of 8 mixed prompts (768 -> 1536), equal on the 32k-token prompt (1024 -> 2048);
     // beyond that the wide form re-reads the window rows half as often.  Same bits either way.
-    const bool narrow = g_imp_keys ? g_imp_keys == pdd::kImpBK / 2 : blocks <= 4 * (int64_t)compute_units();
+    // (Counted in workgroups that have keys: the grid is sized for the longest sequence.)
+    const int64_t working = (int64_t)d->total_k / pdd::kImpBK * d->n_kv_heads * p.n_split;
+    const bool narrow = g_imp_keys ? g_imp_keys == pdd::kImpBK / 2 : working <= 4 * (int64_t)compute_units();
     if (narrow) {
         p.n_ktiles = (d->max_seqlen_k + pdd::kImpBK / 2 - 1) / (pdd::kImpBK / 2);
         blocks = (int64_t)p.n_ktiles * d->batch * d->n_kv_heads * p.n_split;
