@@ -381,7 +381,6 @@ void attn_fwd_kernel(const AttnParams p)
     // Scores are pipelined per 32-key block u = 2*tile + blk: while block u goes
     // through softmax and PV, the MFMAs of block u+1 are already issued.  Tile t
     // lives in LDS buffer t % 3; at every tile boundary the current block is in sA.
-    const int n_blocks = 2 * n_tiles;
     f32x16 sA = zero16, sB = zero16;
     if (n_tiles > 0) qk_block(0, sA);   // every wave has rows that see block 0
     __builtin_amdgcn_s_waitcnt(0);
