@@ -9,7 +9,9 @@
 //
 // Work decomposition
 //   workgroup = NWAVES wavefronts, each owning 32 consecutive queries of one
-//   (sequence, query head); key/value tiles of 64 keys stream through LDS.
+//   (sequence, query head); a sequence's query tiles are aligned to its end, so
+//   that rows a ragged length leaves empty fall into the tile with the fewest
+//   keys; key/value tiles of 64 keys stream through LDS.
 //   Per 32-key block a wave computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16
 //   (A = K rows from LDS, B = Q fragments held in registers), so lane l owns
 //   query (l % 32) and the 16 accumulator registers hold 16 different keys:
@@ -184,12 +186,17 @@ void attn_fwd_kernel(const AttnParams p)
     const int qs = min(p.cu_q[b], p.total_q), qe = min(p.cu_q[b + 1], p.total_q);
     const int ks = min(p.cu_k[b], p.total_k), ke = min(p.cu_k[b + 1], p.total_k);
     const int nq = qe - qs, nk = ke - ks;
-    const int m0 = t * BM;
+    // The sequence's query tiles are aligned to its END: tile t of n_qt holds rows m0 .. m0 + BM - 1
+    // with m0 = nq - (n_qt - t) BM, and where nq is not a multiple of BM the rows below 0, which
+    // do not exist, fall into tile 0, the workgroup with the fewest keys (aligned to the start,
+    // the empty rows would sit in the last tile and ride along through all of its key tiles).
+    const int n_qt = (nq + BM - 1) / BM;
+    const int m0 = nq - (n_qt - t) * BM;
     const int tid = threadIdx.x;
     // importance sweep: this workgroup's slice of the partial column sums, at its sequence
     float *const part_row = IMP
         ? p.imp_part + ((int64_t)(hg * p.n_qtiles + t) * p.Hkv + g) * p.total_k + ks : nullptr;
-    if (m0 >= nq || nq <= 0) {
+    if (t >= n_qt || nq <= 0) {
         if constexpr (IMP)   // no query rows here: the slice still has to read as zero
             for (int j = tid; j < nk; j += NWAVES * 64) part_row[j] = 0.f;
         return;
@@ -202,11 +209,11 @@ void attn_fwd_kernel(const AttnParams p)
 
     const int wave_q0 = m0 + 32 * wave;
     const int qrow = wave_q0 + n;
-    const int qrow_c = min(qrow, nq - 1);
+    const int qrow_c = max(qrow, 0);               // a row that does not exist computes like row 0; nothing of it is stored
     const int lim = qrow_c + delta;
-    const int wave_lim_max = min(wave_q0 + 31, nq - 1) + delta;
-    const int wave_lim_min = min(wave_q0, nq - 1) + delta;
-    const int kend = min(nk, min(m0 + BM, nq) + delta);
+    const int wave_lim_max = max(wave_q0 + 31, 0) + delta;
+    const int wave_lim_min = max(wave_q0, 0) + delta;
+    const int kend = min(nk, m0 + BM + delta);
     const int n_tiles = kend > 0 ? (kend + kBN - 1) / kBN : 0;
 
     // ---- buffer resources over this sequence's K / V rows of KV head g
@@ -277,21 +284,23 @@ void attn_fwd_kernel(const AttnParams p)
     // through LDS in the layout of half a K tile (read per lane from global memory, a row per
     // lane, every load instruction touches 32 rows 32 bytes at a time and the loads of a
     // workgroup take longer than the first K and V tiles).  They land in buffers that the first
-    // K and V requests below leave alone; rows past the sequence's end read as zero.
+    // K and V requests below leave alone; rows below 0 read row 0 (a wave without rows: zeros).
     // tile-sized LDS slots 2, 4, 5, 6 (K buffer 2, V buffers 1 and 2, one behind them), two waves each
     const uint32_t q_lds_off = (uint32_t)((wave < 2 ? 2 : 3 + (wave >> 1)) * kTileBytes + (wave & 1) * 32 * ROWB);
     bf16x8 qf[NKK];
     auto issue_q = [&]() {
-        const uint16_t *qbase = p.q + (int64_t)(qs + wave_q0) * p.q_st + (int64_t)h * p.q_sh;
+        const int q_first = max(wave_q0, 0);        // the wave's first existing row
+        const uint16_t *qbase = p.q + (int64_t)(qs + q_first) * p.q_st + (int64_t)h * p.q_sh;
         const uint32_t q_row_bytes = (uint32_t)p.q_st * 2u;
-        const int q_rows = min(32, nq - wave_q0);
+        const int q_rows = wave_q0 + 32 - q_first;
         const uint32_t q_span = q_rows > 0 ? (uint32_t)(q_rows - 1) * q_row_bytes + (uint32_t)ROWB : 0u;
         const i32x4 rs = make_rsrc(qbase, q_span);
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i) {
             const int r = RPI * i + lane / CH;
             const int c = (lane % CH) ^ swz_row<D>(r);
-            dma16_to_lds(rs, ks_lds + q_lds_off + 1024 * i, (uint32_t)r * q_row_bytes + (uint32_t)c * 16u);
+            const int r_rel = max(wave_q0 + r - q_first, 0);
+            dma16_to_lds(rs, ks_lds + q_lds_off + 1024 * i, (uint32_t)r_rel * q_row_bytes + (uint32_t)c * 16u);
         }
     };
 
@@ -387,8 +396,9 @@ void attn_fwd_kernel(const AttnParams p)
     __syncthreads();                    // V tile 0, K tile 1; the next requests overwrite the Q rows
 
     // ---- hot tiles: those that no wave of the workgroup has to mask (fully visible to the
-    // workgroup's first query: 64 (t+1) - 1 <= m0 + delta) and that have a successor tile.
-    const int first_lim = m0 + delta;
+    // workgroup's first existing query: 64 (t+1) - 1 <= max(m0, 0) + delta) and that have a
+    // successor tile.
+    const int first_lim = max(m0, 0) + delta;
     const int n_hot = max(0, min((first_lim + 1) / kBN, n_tiles - 1));   // tiles 0 .. n_hot-1
 
     // The block `cur` arrives in the log2 domain (see above): the scale-and-shift and the row max
@@ -591,9 +601,9 @@ void attn_fwd_kernel(const AttnParams p)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // all reads before the first store
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i)
-            if (wave_q0 + RPI * i + sr < nq) *(u32x4 *)(op + (int64_t)(RPI * i) * p.o_st) = x[i];
+            if (wave_q0 + RPI * i + sr >= 0) *(u32x4 *)(op + (int64_t)(RPI * i) * p.o_st) = x[i];
     }
-    if (qrow < nq && hh == 0) {
+    if (qrow >= 0 && hh == 0) {
         const float lse = l_tot > 0.f
             ? (__builtin_amdgcn_logf(l_tot) - ref) * 0.6931471805599453f
             : -INFINITY;
@@ -619,7 +629,7 @@ void attn_fwd_kernel(const AttnParams p)
         float *lse_sh = (float *)(smem_attn + kSweepBufs * kTileBytes);          // [NWAVES][32]
         float *red = (float *)(smem_attn + kSweepBufs * kTileBytes + 1024);      // [2][64][NWAVES]
         // a row's probabilities are 2^(s * c2 - lse2); rows past the end or without a visible key give 0
-        const float lse2 = (qrow < nq && l_tot > 0.f) ? __builtin_amdgcn_logf(l_tot) - ref : INFINITY;
+        const float lse2 = (qrow >= 0 && l_tot > 0.f) ? __builtin_amdgcn_logf(l_tot) - ref : INFINITY;
         if (hh == 0) lse_sh[wave * 32 + n] = lse2;
         for (int tl = 0; tl < kSweepAhead; ++tl) issue_k(tl, tl);   // tiles past the end read as zero
         __builtin_amdgcn_s_waitcnt(0);
