@@ -370,6 +370,29 @@ void attn_fwd_kernel(const AttnParams p)
         thr = up ? kLazyLog2 : thr;
     };
 
+    // A wave all of whose rows lie below 0 (a chunk or a first tile shorter than the workgroup)
+    // has nothing to compute or store: it only makes its share of the K and V requests and meets
+    // the others at their barriers, two before the first tile and one per tile, and leaves the
+    // matrix pipe to the waves with rows.  (With the importance sweep the wave stays on the
+    // common path: the sweep needs it as one of the waves that add up a tile's column sums.)
+    if constexpr (!IMP) {
+        if (wave_q0 + 31 < 0) {
+            if (n_tiles > 0) issue_k(0, 0);
+            if (n_tiles > 0) issue_v(0, 0);
+            if (n_tiles > 1) issue_k(1, 1);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            __syncthreads();
+            for (int it = 0; it < n_tiles; ++it) {
+                if (it + 1 < n_tiles) issue_v(it + 1, (it + 1) % 3);
+                if (it + 2 < n_tiles) issue_k(it + 2, (it + 2) % 3);
+                __builtin_amdgcn_s_waitcnt(0);
+                __syncthreads();
+            }
+            return;
+        }
+    }
+
     // Requests in the order of their first use.  The first barrier waits for K tile 0 and the Q
     // rows only (loads return in order: the younger requests may still be open); the first QK
     // block runs while V tile 0 and K tile 1 arrive, and the second barrier publishes those.
