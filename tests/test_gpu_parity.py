@@ -109,6 +109,33 @@ def test_random_shapes(seed):
                     label=f"random {seed}: q={lens_q} chunked={chunked} heads={hq}/{hkv} d={d}")
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_short_chunks_behind_a_long_prefix(d):
+    """Chunks much shorter than a workgroup (1 to 224 new tokens behind about 5000 keys): most
+    waves of a workgroup have no rows and only take part in the K/V requests and the barriers of
+    the pipelined and the masked loop; with the library's scratch the importance sweep keeps them
+    on the common path.  128 and 256 query rows per workgroup, everything against the oracle."""
+    lens_q = [1, 40, 100, 224, 33]
+    lens_k = [q + 5000 + 37 * i for i, q in enumerate(lens_q)]
+    wl = W.make_custom("t", lens_q, lens_k, 8, 2, d, 0, "1/4", seed=90 + d, chunked=True)
+    oO, oL = oracle.attention(wl.q, wl.k, wl.v, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale)
+    oI = oracle.importance(wl.q, wl.k, wl.cu_seqlens_q, wl.cu_seqlens_k, wl.scale, -1)
+    try:
+        for waves in (4, 8):
+            pdd.set_option(pdd.OPT_ATTN_WAVES, waves)
+            dev = DeviceWorkload(wl)
+            for use_ws in (False, True):
+                what = f"d={d} waves={waves} scratch={use_ws}"
+                dev.poison()
+                dev.attn(True, use_workspace=use_ws)
+                O, lse, imp = dev.results()[:3]
+                assert np.abs(O - oO).max() <= O_ATOL, what + " O"
+                rel_close(lse, oL, what + " lse")
+                rel_close(imp, oI, what + " importance")
+    finally:
+        pdd.set_option(pdd.OPT_ATTN_WAVES, 0)
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_random_chunks_with_long_prefix(seed):
     """Seeded random chunked problems with several query tiles and prefixes of up to 3000 keys, so
