@@ -143,8 +143,11 @@ pdd_status pdd_prefill_attn(const pdd_attn_desc *desc, const void *q, const void
  * its queries it walks its K tiles a second time, with Q still in registers,
  * and leaves the column sums of its probabilities in the workspace; a short
  * second kernel adds them over the heads of a group and the query tiles in a
- * fixed order.  Shapes that would need more than 256 MiB for this and calls
- * that are given less use the separate importance kernel described above.  All forms are deterministic and agree to fp32 rounding.
+ * fixed order.  Shapes that would need more than 256 MiB for this, chunks
+ * whose longest fills less than 70 % of its query tiles (the second walk costs
+ * what full tiles cost) and calls that are given less use the separate
+ * importance kernel described above; pdd_workspace_bytes says what the shape
+ * will use.  All forms are deterministic and agree to fp32 rounding.
  */
 pdd_status pdd_prefill_attn_chunked(const pdd_attn_desc *desc, const void *q_chunk,
                                     const void *k_all, const void *v_all, void *o, float *lse,
