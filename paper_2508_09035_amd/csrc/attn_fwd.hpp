@@ -276,6 +276,9 @@ void attn_fwd_kernel(const AttnParams p)
             for (int db = 0; db < NDB; ++db) {
                 const int chunk = 4 * db + 2 * dhalf + ((s16 & 3) >> 1);
                 vaddr[db][eg] = vs_lds + (uint32_t)(row * ROWB + (chunk ^ swz_row<D>(row)) * 16) + 8u * (s16 & 1);
+                // kept as one value each: left to itself the compiler splits an address into a part
+                // per read group and a part per dim block and adds the two again before every read
+                asm volatile("" : "+v"(vaddr[db][eg]));
             }
         }
     }
