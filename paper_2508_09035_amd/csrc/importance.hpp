@@ -140,11 +140,15 @@ void importance_kernel(const ImpParams p)
             qrow_l[ci] = r;
             qvoff[ci] = (uint32_t)c * 16u;
         }
-        auto issue_item = [&](int item_local, int buf) {
-            const int item = item0 + item_local;
-            const int hg = item / (n_rb - rb_first), rb = rb_first + item % (n_rb - rb_first);
-            const int h = g * p.G + hg;
-            const int i0 = iw0 + 32 * rb;
+        // Blocks are requested and worked on in order, so the (head, row block) pair of the next
+        // request and the row block in work are counted along: one division here, none per block.
+        const int n_rbs = n_rb - rb_first;           // row blocks per head that this workgroup walks
+        int iss_hg = n_rbs > 0 ? item0 / n_rbs : 0, iss_rb = n_rbs > 0 ? item0 % n_rbs : 0;
+        int cur_rb = iss_rb;
+        auto issue_item = [&](int buf) {              // the next block in order
+            const int h = g * p.G + iss_hg;
+            const int i0 = iw0 + 32 * (rb_first + iss_rb);
+            if (++iss_rb == n_rbs) { iss_rb = 0; ++iss_hg; }
 #pragma unroll
             for (int ci = 0; ci < NLD; ++ci) {
                 const int i = min(i0 + qrow_l[ci], nq - 1);
@@ -167,7 +171,7 @@ void importance_kernel(const ImpParams p)
         // wait then ends both (the blocks were requested together and land together).  With the K
         // loads done here the compiler places no load waits inside the loop, where they would also
         // wait for the asynchronous row-block transfers in flight.
-        for (int i = 0; i < kImpAhead && i < n_items; ++i) issue_item(i, i);
+        for (int i = 0; i < kImpAhead && i < n_items; ++i) issue_item(i);
         __builtin_amdgcn_s_waitcnt(0);
         for (int item = 0; item < n_items; ++item) {
             const int buf = item & (kImpBufs - 1);
@@ -177,9 +181,9 @@ void importance_kernel(const ImpParams p)
             else if (newer == 1) wait_vmcnt<PER_ITEM>();
             else wait_vmcnt<0>();
             __syncthreads();     // every wave's part of the block has landed; the buffer refilled below is free
-            if (item + kImpAhead < n_items) issue_item(item + kImpAhead, (item + kImpAhead) & (kImpBufs - 1));
-            const int rb = rb_first + (item0 + item) % (n_rb - rb_first);
-            const int i0 = iw0 + 32 * rb;
+            if (item + kImpAhead < n_items) issue_item((item + kImpAhead) & (kImpBufs - 1));
+            const int i0 = iw0 + 32 * (rb_first + cur_rb);
+            if (++cur_rb == n_rbs) cur_rb = 0;
             const int i_last = min(i0 + 31, nq - 1);
             if (jw0 <= i_last + delta && jw0 < nk) {       // some row of the block sees some key of the wave
                 const uint8_t *qb = &qs_lds[buf][0];
