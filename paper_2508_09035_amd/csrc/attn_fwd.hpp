@@ -517,6 +517,9 @@ void attn_fwd_kernel(const AttnParams p)
                 __builtin_amdgcn_sched_group_barrier(0x100, (NKK + NA - 1) / NA, 0);  // DS reads
                 __builtin_amdgcn_sched_group_barrier(0x002, (32 + NA - 1) / NA, 0);   // VALU
             }
+            // the row sums are complete here (left alone, their additions sink behind the branch and
+            // pile up after the last two MFMAs)
+            asm volatile("" : "+v"(l_part[0]), "+v"(l_part[1]), "+v"(l_part[2]), "+v"(l_part[3]));
             if (hidden) {
                 asm volatile("" ::: "memory");     // stays a branch
 #pragma unroll
